@@ -1,0 +1,128 @@
+/*
+ * spa2 — C ABI of the SpargeAttention2 hot path on AMD MI355X (gfx950).
+ *
+ * Three operations, split at the two seams of the paper's operator
+ * O = SpargeAttn2(Q, K, V, k%, p%)  (Sec. 4.3, Alg. 1):
+ *
+ *   spa2_mask : Alg. 1 steps 2-6.  Mean-pools Q and K per block, forms the
+ *               pooled map Pbar = softmax(Qbar Kbar^T * scale) (Sec. 2.2) and
+ *               selects, per row, Top-k UNION Top-p (Sec. 4.1 equation).
+ *   spa2_fwd  : Alg. 1 steps 7-21.  FlashAttention-style online softmax over
+ *               the selected (query block, key block) tiles only (Sec. 2.1).
+ *   spa2_bwd  : gradients of spa2_fwd's O w.r.t. Q, K, V over the same tiles
+ *               (Sec. 4.3 says a backward pass exists; the mask is constant).
+ *
+ * Conventions common to every entry point
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller.  The
+ *     library never allocates, frees or keeps device memory and holds no
+ *     global state.  bf16 tensors are raw 16-bit storage.
+ *   - Calls enqueue work on `stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream) and return without synchronising.
+ *   - Return value: SPA2_OK (0) or a negative SPA2_ERR_* code.  All argument
+ *     checks happen before the first launch, so a failed call leaves every
+ *     output untouched.  No C++ exception crosses this boundary.
+ *   - Block sizes are b_q = 128 query tokens and b_kv = 64 key/value tokens
+ *     (App. A).  T_m = ceil(N / 128), T_n = ceil(N / 64); a short last block
+ *     is handled (pooled over its valid tokens, padded keys excluded from the
+ *     softmax, padded query rows never stored).
+ *   - Token tensors (Q, K, V, O, dO, dQ, dK, dV) share one layout given by
+ *     spa2_shape: element (b, h, n, c) lives at b*sb + h*sh + n*sn + c, the
+ *     head dimension is contiguous, base pointers are 16-byte aligned and
+ *     sb, sh, sn are multiples of 8 elements.  [B,H,N,d] and [B,N,H,d] both
+ *     fit.  Per-row vectors (LSE) and the pattern arrays are contiguous.
+ */
+#ifndef SPA2_H
+#define SPA2_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SPA2_BQ  128
+#define SPA2_BKV 64
+/* longest row of key blocks the masker sorts in one workgroup (N <= 524288) */
+#define SPA2_MAX_TN 8192
+
+enum {
+  SPA2_OK = 0,
+  SPA2_ERR_NULL = -1,         /* a required pointer is NULL */
+  SPA2_ERR_SHAPE = -2,        /* B, H, N, d <= 0, or N too long for the masker */
+  SPA2_ERR_UNSUPPORTED = -3,  /* d not in {64, 128}, or block sizes other than 128 / 64 */
+  SPA2_ERR_ALIGN = -4,        /* pointer not 16-byte aligned or stride not a multiple of 8 */
+  SPA2_ERR_RANGE = -5,        /* topk_blocks outside [0, T_n], top_p outside [0, 1], both zero, scale <= 0 */
+  SPA2_ERR_WORKSPACE = -6,    /* workspace missing or smaller than spa2_*_workspace_bytes */
+  SPA2_ERR_LAUNCH = -7        /* the HIP runtime refused a launch (hipGetLastError) */
+};
+
+typedef struct spa2_shape {
+  int32_t B, H, N, d;   /* d in {64, 128}; self-attention: Q, K, V all have N tokens */
+  int32_t bq, bkv;      /* must be 128 and 64 */
+  int64_t sb, sh, sn;   /* element strides of batch, head, token */
+} spa2_shape;
+
+/* Block-sparse pattern.  `mask` is the paper's Mbar (Sec. 2.2); the index lists
+ * are the same information in the two orders the kernels walk it. */
+typedef struct spa2_pattern {
+  uint8_t* mask;      /* [B,H,T_m,T_n] 0/1                                          */
+  int32_t* row_cnt;   /* [B,H,T_m]      number of selected key blocks of a query block */
+  int32_t* row_idx;   /* [B,H,T_m,T_n]  first row_cnt entries valid, ascending j      */
+  int32_t* col_cnt;   /* [B,H,T_n]      number of query blocks that selected key block j */
+  int32_t* col_idx;   /* [B,H,T_n,T_m]  first col_cnt entries valid, ascending i      */
+} spa2_pattern;
+
+int spa2_version(void);
+const char* spa2_strerror(int code);
+
+/* Host helper: the number of blocks that "the k% largest positions" (Sec. 2.2,
+ * Top-k) means for a row of T_n blocks: 0 if k_frac <= 0, otherwise
+ * ceil(k_frac * T_n) clamped to [1, T_n].  Case 1 of Sec. 3.2 (Top-20% of ten
+ * entries keeps two) fixes the integral case. */
+int32_t spa2_topk_blocks(double k_frac, int32_t Tn);
+
+/* Bytes of device scratch spa2_mask / spa2_bwd need for this shape. */
+size_t spa2_mask_workspace_bytes(const spa2_shape* shape);
+size_t spa2_bwd_workspace_bytes(const spa2_shape* shape);
+
+/* Alg. 1 steps 2-6 (Sec. 2.2 pooling and pooled map, Sec. 4.1 hybrid rule).
+ *   q, k        bf16 token tensors (device).
+ *   topk_blocks Top-k block count per row, from spa2_topk_blocks; 0 = Top-p only.
+ *   top_p       cumulative-probability threshold in [0, 1]; 0 = Top-k only.
+ *   scale       multiplies Qbar Kbar^T (1/sqrt(d) in the paper).
+ *   out         all five arrays are written (col_* may be NULL if no backward follows).
+ *   pbar_out    optional fp32 [B,H,T_m,T_n]: the pooled map the selection was taken on.
+ * Per row: entries are ordered by (Pbar descending, block index ascending);
+ * n_p is the shortest prefix whose sum (accumulated in fp64, in that order)
+ * is >= top_p; the first max(1, topk_blocks, n_p) entries are selected. */
+int spa2_mask(const void* q, const void* k, const spa2_shape* shape,
+              int32_t topk_blocks, float top_p, float scale,
+              spa2_pattern* out, float* pbar_out,
+              void* workspace, size_t workspace_bytes, void* stream);
+
+/* Fills `out` with the all-ones pattern (every tile selected): dense attention
+ * through the same kernels, and the sparsity-0 special case. */
+int spa2_pattern_full(const spa2_shape* shape, spa2_pattern* out, void* stream);
+
+/* Alg. 1 steps 7-21.  For every query block i, over the key blocks j listed in
+ * pattern->row_idx only: S_ij = Q_i K_j^T * scale, running row maximum and sum,
+ * O_i accumulated in fp32 and divided by the final sum.
+ *   o    bf16 token tensor (written);  lse fp32 [B,H,N] = log sum_j exp(S) per row (written).
+ * Reads pattern->row_cnt / row_idx. */
+int spa2_fwd(const void* q, const void* k, const void* v, const spa2_shape* shape,
+             const spa2_pattern* pattern, float scale, void* o, float* lse, void* stream);
+
+/* Backward of spa2_fwd for upstream gradient d_o, mask held constant.  With
+ * P = exp(S - lse) on selected tiles:  dV = P^T dO,  dP = dO V^T,
+ * D = rowsum(dO * O),  dS = P * (dP - D),  dQ = dS K * scale,  dK = dS^T Q * scale.
+ *   dq, dk, dv  bf16 token tensors (written everywhere, zeros where no tile contributes).
+ * Reads row_* (dQ) and col_* (dK, dV) of the pattern; workspace holds D. */
+int spa2_bwd(const void* q, const void* k, const void* v, const void* o, const void* d_o,
+             const float* lse, const spa2_shape* shape, const spa2_pattern* pattern, float scale,
+             void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPA2_H */

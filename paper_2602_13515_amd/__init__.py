@@ -1,0 +1,10 @@
+"""spa2: SpargeAttention2's hot path (hybrid Top-k+Top-p block masker, block-sparse
+attention forward and backward) as hand-written HIP kernels for AMD MI355X (gfx950).
+
+`binding` exposes the C ABI of libspa2.so one-to-one; `workloads` holds the seeded
+synthetic input recipes; `build` compiles the library in-tree with hipcc.
+"""
+from .binding import (  # noqa: F401
+    BKV, BQ, Pattern, Spa2Error, alloc_pattern, spa2_bwd, spa2_bwd_workspace_bytes, spa2_fwd, spa2_mask,
+    spa2_mask_workspace_bytes, spa2_pattern_full, spa2_strerror, spa2_topk_blocks, spa2_version,
+)

@@ -1,0 +1,91 @@
+// Device-side helpers shared by the spa2 kernels (gfx950 / CDNA4, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace spa2 {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+constexpr int BQ = 128;
+constexpr int BKV = 64;
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LN2 = 0.6931471805599453f;
+
+// Operand layouts of the two bf16 MFMA shapes used here (lane l of a wave64):
+//   32x32x16:  A[m][k]: m = l%32, k = 8*(l/32)+s (s=0..7)   B[k][n]: n = l%32, same k
+//              C[m][n]: n = l%32, m = 8*(v/4) + 4*(l/32) + v%4 for accumulator register v = 0..15
+//   16x16x32:  A[m][k]: m = l%16, k = 8*(l/16)+s            B[k][n]: n = l%16, same k
+//              C[m][n]: n = l%16, m = 4*(l/16) + v for v = 0..3
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
+// Two floats -> packed bf16 pair (round to nearest even), low half = a.
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+  f32x2 v = {a, b};
+  bf16x2 r = __builtin_convertvector(v, bf16x2);
+  return __builtin_bit_cast(uint32_t, r);
+}
+
+__device__ __forceinline__ bf16x8 make_bf16x8(float x0, float x1, float x2, float x3,
+                                              float x4, float x5, float x6, float x7) {
+  u32x4 u = {pack_bf16(x0, x1), pack_bf16(x2, x3), pack_bf16(x4, x5), pack_bf16(x6, x7)};
+  return __builtin_bit_cast(bf16x8, u);
+}
+
+__device__ __forceinline__ float bf16_to_float(uint16_t x) {
+  return __builtin_bit_cast(float, (uint32_t)x << 16);
+}
+
+// Transposing LDS read (ds_read_b64_tr_b16).  Within each group of 16 lanes,
+// lane s supplies the address of four consecutive 16-bit elements; lane i of
+// the group receives element (i%4) of the data addressed by lanes i/4, 4+i/4,
+// 8+i/4, 12+i/4.  If lane s points at row (s/4), columns 4*(s%4).. of a
+// row-major tile, lane i ends up with column i of rows 0..3: a 4x16 patch read
+// column-wise, which is what an MFMA operand needs when the contraction index
+// is the row of the tile in memory.
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+__device__ __forceinline__ u32x2 lds_read_tr4(const uint16_t* lds_ptr) {
+  s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(lds_ptr));
+  return __builtin_bit_cast(u32x2, v);
+}
+__device__ __forceinline__ bf16x8 join_tr(u32x2 lo, u32x2 hi) {
+  u32x4 u = {lo[0], lo[1], hi[0], hi[1]};
+  return __builtin_bit_cast(bf16x8, u);
+}
+
+// Exchange between the two 32-lane halves of a wave: returns, in every lane,
+// the value held by the lane 32 positions away.
+__device__ __forceinline__ float other_half(float x) {
+  return __shfl_xor(x, 32, 64);
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// Workgroup id -> (head, block) mapping that keeps one head's blocks resident
+// on all eight XCDs at once: consecutive workgroup ids go round-robin to the
+// XCDs, so XCD x receives ids x, x+8, ...; those are given a contiguous chunk
+// of the head's blocks, which share K/V tiles through that XCD's L2.
+struct HeadBlock { int bh; int blk; bool valid; };
+__device__ __forceinline__ HeadBlock xcd_map(int wg, int blocks_per_head, int chunk) {
+  const int xcd = wg & 7;
+  const int slot = wg >> 3;
+  HeadBlock r;
+  r.bh = slot / chunk;
+  r.blk = xcd * chunk + slot % chunk;
+  r.valid = r.blk < blocks_per_head;
+  return r;
+}
+
+}  // namespace spa2

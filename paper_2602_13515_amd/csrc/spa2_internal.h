@@ -1,0 +1,44 @@
+// Host-side declarations shared by the spa2 translation units (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "spa2.h"
+
+namespace spa2 {
+
+struct Dims {
+  int B, H, N, d, Tm, Tn;
+  int64_t sb, sh, sn;
+};
+
+inline Dims make_dims(const spa2_shape& s) {
+  Dims m;
+  m.B = s.B; m.H = s.H; m.N = s.N; m.d = s.d;
+  m.Tm = (s.N + SPA2_BQ - 1) / SPA2_BQ;
+  m.Tn = (s.N + SPA2_BKV - 1) / SPA2_BKV;
+  m.sb = s.sb; m.sh = s.sh; m.sn = s.sn;
+  return m;
+}
+
+// Each launcher enqueues its kernels on `stream` and returns hipGetLastError().
+hipError_t launch_pool(const void* q, const void* k, const Dims& m, float* qbar, float* kbar, hipStream_t stream);
+hipError_t launch_select(const float* qbar, const float* kbar, const Dims& m, int topk_blocks, float top_p,
+                         float scale, uint8_t* mask, int32_t* row_cnt, int32_t* row_idx, float* pbar_out,
+                         hipStream_t stream);
+hipError_t launch_columns(const uint8_t* mask, const Dims& m, int32_t* col_cnt, int32_t* col_idx,
+                          hipStream_t stream);
+hipError_t launch_pattern_full(const Dims& m, uint8_t* mask, int32_t* row_cnt, int32_t* row_idx,
+                               int32_t* col_cnt, int32_t* col_idx, hipStream_t stream);
+hipError_t launch_fwd(const void* q, const void* k, const void* v, const Dims& m, const int32_t* row_cnt,
+                      const int32_t* row_idx, float scale, void* o, float* lse, hipStream_t stream);
+hipError_t launch_bwd_delta(const void* o, const void* d_o, const Dims& m, float* delta, hipStream_t stream);
+hipError_t launch_bwd_dq(const void* q, const void* k, const void* v, const void* d_o, const float* lse,
+                         const float* delta, const Dims& m, const int32_t* row_cnt, const int32_t* row_idx,
+                         float scale, void* dq, hipStream_t stream);
+hipError_t launch_bwd_dkdv(const void* q, const void* k, const void* v, const void* d_o, const float* lse,
+                           const float* delta, const Dims& m, const int32_t* col_cnt, const int32_t* col_idx,
+                           float scale, void* dk, void* dv, hipStream_t stream);
+
+}  // namespace spa2

@@ -1,0 +1,156 @@
+"""Host-side checks that need no GPU: the shared library loads, exports every symbol the
+header declares, validates its arguments before any launch, and the k% -> block-count rule
+agrees with the oracle's."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import spa2_oracle as orc
+from paper_2602_13515_amd import binding
+from paper_2602_13515_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "spa2.h")
+
+
+def _declared():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(spa2_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = binding._load()
+    names = _declared()
+    assert set(names) == set(binding.EXPORTED_SYMBOLS), names
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_version_and_error_strings():
+    assert binding.spa2_version() >= 100
+    seen = set()
+    for code in range(0, -8, -1):
+        s = binding.spa2_strerror(code)
+        assert s and s not in seen
+        seen.add(s)
+    assert "unknown" in binding.spa2_strerror(-99)
+
+
+def test_topk_blocks_matches_oracle_rule():
+    for tn in (1, 2, 7, 10, 32, 512, 1182, 4096):
+        for k in (0.0, 1e-9, 0.01, 0.03, 0.05, 0.1, 0.2, 0.25, 0.5, 0.999, 1.0, 2.0):
+            assert binding.spa2_topk_blocks(k, tn) == orc.topk_blocks(k, tn), (k, tn)
+    assert binding.spa2_topk_blocks(0.2, 10) == 2          # Case 1 of Sec. 3.2
+    assert binding.spa2_topk_blocks(0.05, 1182) == 60
+
+
+def _shape(B=1, H=2, N=300, d=128, bq=128, bkv=64, sb=None, sh=None, sn=None):
+    sn = d if sn is None else sn
+    sh = N * sn if sh is None else sh
+    sb = H * sh if sb is None else sb
+    return binding._Shape(B, H, N, d, bq, bkv, sb, sh, sn)
+
+
+def test_argument_validation_happens_on_the_host():
+    """Every rejected call returns before touching the device (there is none here)."""
+    lib = binding._load()
+    pat = binding._Pattern(None, None, None, None, None)
+    fake = ctypes.c_void_p(0x1000)           # 16-byte aligned, never dereferenced on these paths
+    odd = ctypes.c_void_p(0x1004)
+    ok = _shape()
+    f = lib.spa2_fwd
+    assert f(None, fake, fake, ctypes.byref(ok), ctypes.byref(pat), 0.1, fake, fake, None) == -1
+    assert f(fake, fake, fake, None, ctypes.byref(pat), 0.1, fake, fake, None) == -1
+    assert f(fake, fake, fake, ctypes.byref(ok), ctypes.byref(pat), 0.1, fake, fake, None) == -1   # empty pattern
+    full = binding._Pattern(0x1000, 0x1000, 0x1000, 0x1000, 0x1000)
+    assert f(odd, fake, fake, ctypes.byref(ok), ctypes.byref(full), 0.1, fake, fake, None) == -4
+    assert f(fake, fake, fake, ctypes.byref(ok), ctypes.byref(full), 0.0, fake, fake, None) == -5
+    assert f(fake, fake, fake, ctypes.byref(_shape(d=96)), ctypes.byref(full), 0.1, fake, fake, None) == -3
+    assert f(fake, fake, fake, ctypes.byref(_shape(bq=64)), ctypes.byref(full), 0.1, fake, fake, None) == -3
+    assert f(fake, fake, fake, ctypes.byref(_shape(N=0)), ctypes.byref(full), 0.1, fake, fake, None) == -2
+    assert f(fake, fake, fake, ctypes.byref(_shape(sn=132)), ctypes.byref(full), 0.1, fake, fake, None) == -4
+    m = lib.spa2_mask
+    big = 1 << 30
+    assert m(fake, fake, ctypes.byref(ok), 1, 0.5, 0.1, ctypes.byref(full), None, None, big, None) == -6
+    assert m(fake, fake, ctypes.byref(ok), 1, 0.5, 0.1, ctypes.byref(full), None, fake, 16, None) == -6
+    assert m(fake, fake, ctypes.byref(ok), 0, 0.0, 0.1, ctypes.byref(full), None, fake, big, None) == -5
+    assert m(fake, fake, ctypes.byref(ok), 6, 0.5, 0.1, ctypes.byref(full), None, fake, big, None) == -5   # Tn = 5
+    assert m(fake, fake, ctypes.byref(ok), 1, 1.5, 0.1, ctypes.byref(full), None, fake, big, None) == -5
+    assert m(fake, fake, ctypes.byref(ok), 1, float("nan"), 0.1, ctypes.byref(full), None, fake, big, None) == -5
+    assert m(fake, fake, ctypes.byref(_shape(N=64 * 8193, d=64)), 1, 0.5, 0.1, ctypes.byref(full), None, fake,
+             1 << 40, None) == -2                                                                      # row too long
+    half = binding._Pattern(0x1000, 0x1000, 0x1000, 0x1000, None)
+    assert m(fake, fake, ctypes.byref(ok), 1, 0.5, 0.1, ctypes.byref(half), None, fake, big, None) == -1
+    b = lib.spa2_bwd
+    norows = binding._Pattern(0x1000, 0x1000, 0x1000, None, None)
+    args = [fake] * 6
+    assert b(*args, ctypes.byref(ok), ctypes.byref(norows), 0.1, fake, fake, fake, fake, big, None) == -1
+    assert b(*args, ctypes.byref(ok), ctypes.byref(full), 0.1, fake, fake, fake, fake, 8, None) == -6
+    assert lib.spa2_pattern_full(ctypes.byref(ok), None, None) == -1
+
+
+def test_workspace_sizes():
+    lib = binding._load()
+    s = _shape(B=2, H=3, N=1000, d=128)
+    tm, tn = 8, 16
+    need = lib.spa2_mask_workspace_bytes(ctypes.byref(s))
+    assert need >= 6 * (tm + tn) * 128 * 4 and need % 256 == 0
+    assert lib.spa2_bwd_workspace_bytes(ctypes.byref(s)) >= 6 * 1000 * 4
+    assert lib.spa2_mask_workspace_bytes(ctypes.byref(_shape(d=100))) == 0
+
+
+def test_binding_rejects_bad_tensors_before_calling_c():
+    import torch
+    q = torch.zeros((1, 1, 128, 128), dtype=torch.float32)
+    with pytest.raises(ValueError):
+        binding._shape_of(q)
+    with pytest.raises(ValueError):
+        binding._shape_of(torch.zeros((1, 128, 128), dtype=torch.bfloat16))
+    with pytest.raises(ValueError):
+        binding._shape_of(torch.zeros((1, 1, 128, 128), dtype=torch.bfloat16).transpose(2, 3))
+
+
+# ------------------------------------------------------------------ workload generators
+def test_workload_shapes_and_determinism():
+    assert (wl.WAN13_95.Tm, wl.WAN13_95.Tn) == (256, 512)
+    assert (wl.WAN14_95.Tm, wl.WAN14_95.Tn) == (591, 1182)
+    assert (wl.TINY.Tm, wl.TINY.Tn) == (16, 32)
+    a = wl.make_inputs(wl.TINY, seed=0)
+    b = wl.make_inputs(wl.TINY, seed=0)
+    c = wl.make_inputs(wl.TINY, seed=1)
+    import torch
+    for x, y in zip(a, b):
+        assert x.dtype == torch.bfloat16 and x.shape == (1, 2, 2048, 64)
+        assert torch.equal(x, y)
+    assert not torch.equal(a[0], c[0])
+    # one head regenerated alone equals the same head of the full draw
+    qh, kh, vh, doh = wl.head_inputs(wl.TINY, 0, 1, seed=0)
+    assert torch.equal(qh, a[0][0, 1]) and torch.equal(doh, a[3][0, 1])
+
+
+def test_lowrank_recipe_gives_skewed_pooled_rows_and_target_sparsity():
+    w = wl.Workload("probe", 1, 1, 8192, 128, 0.05, 0.8, "lowrank", False)
+    q, k, _, _ = wl.head_inputs(w, 0, 0, seed=0, need_do=False)
+    qd, kd = q.double().numpy(), k.double().numpy()
+    sbar = orc.pool(qd, 128) @ orc.pool(kd, 64).T / np.sqrt(128)
+    assert 4.5 < sbar.std() < 7.0                       # pooled logit = 4 * <a_q, a_k>, std about 5.7
+    mask, _ = orc.block_mask(qd, kd, orc.topk_blocks(0.05, w.Tn), 0.8)
+    assert 0.90 < 1.0 - mask.mean() < 0.95
+    # pure Gaussian inputs pool to nearly uniform rows instead
+    g = wl.Workload("g", 1, 1, 8192, 128, 0.05, 0.8, "gaussian", False)
+    q, k, _, _ = wl.head_inputs(g, 0, 0, need_do=False)
+    sb = orc.pool(q.double().numpy(), 128) @ orc.pool(k.double().numpy(), 64).T / np.sqrt(128)
+    assert sb.std() < 0.05
+
+
+def test_stress_recipe_has_uniform_and_sink_rows():
+    w = wl.Workload("probe", 1, 1, 4096, 128, 0.05, 0.8, "stress", False)
+    q, k, _, _ = wl.head_inputs(w, 0, 0, need_do=False)
+    pbar = orc.pooled_map(q.double().numpy(), k.double().numpy())
+    even, odd = pbar[0::2], pbar[1::2]
+    assert np.abs(even * w.Tn - 1).max() < 0.02         # near-uniform rows
+    assert (odd[:, 0] > 0.5).all()                      # the sink block dominates

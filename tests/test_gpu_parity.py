@@ -1,0 +1,201 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 CPU oracle, element by
+element, on seeded inputs small enough for the oracle but spanning several tiles and
+ragged tails."""
+import dataclasses
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2602_13515_amd as spa2
+from oracle import spa2_oracle as orc
+from paper_2602_13515_amd import workloads as wl
+
+from gpu_util import (assert_close, check_pattern_consistency, dev, f64, gpu_bwd, gpu_fwd, gpu_mask,
+                      mask_protocol, pattern_from_mask)
+
+pytestmark = pytest.mark.gpu
+
+
+def _small(name, N, d, kind="gaussian", H=2, B=1, k=0.25, p=0.9):
+    return wl.Workload(name, B, H, N, d, k, p, kind, True)
+
+
+def _random_mask(B, H, N, keep, seed):
+    rng = np.random.default_rng(seed)
+    Tm, Tn = -(-N // 128), -(-N // 64)
+    m = (rng.random((B, H, Tm, Tn)) < keep).astype(np.uint8)
+    for b in range(B):
+        for h in range(H):
+            m[b, h, np.arange(Tm), rng.integers(0, Tn, Tm)] = 1
+    return m
+
+
+FWD_CASES = [
+    ("tiny-d64", wl.TINY, 0.3),
+    ("ragged-d128", _small("ragged128", 1000, 128), 0.4),       # last q block 104 rows, last kv block 40 keys
+    ("ragged-d64", _small("ragged64", 1110, 64), 0.5),          # 86 / 22
+    ("one-block", _small("one", 64, 128, H=1), 1.0),
+    ("short", _small("short", 17, 64, H=1), 1.0),
+]
+
+
+@pytest.mark.parametrize("name,w,keep", FWD_CASES, ids=[c[0] for c in FWD_CASES])
+def test_fwd_bwd_on_given_pattern(name, w, keep):
+    print(f"case {name}: B={w.B} H={w.H} N={w.N} d={w.d}", flush=True)
+    q, k, v, do = wl.make_inputs(w, seed=1)
+    mask = _random_mask(w.B, w.H, w.N, keep, seed=2)
+    qd, kd, vd, dod = (t.to(dev()) for t in (q, k, v, do))
+    pat = pattern_from_mask(mask, dev())
+    o, lse = gpu_fwd(qd, kd, vd, pat)
+    dq, dk, dv = gpu_bwd(qd, kd, vd, o, dod, lse, pat)
+    r_dq, r_dk, r_dv, r_o, r_lse = orc.attention_bwd_bh(f64(q), f64(k), f64(v), mask, f64(do))
+    print("O", assert_close("O", f64(o), r_o))
+    assert np.abs(f64(lse) - r_lse).max() <= 2e-3
+    # gradients: the GPU consumes its own bf16 O and fp32 LSE, as a training step would
+    print("dQ", assert_close("dQ", f64(dq), r_dq))
+    print("dK", assert_close("dK", f64(dk), r_dk))
+    print("dV", assert_close("dV", f64(dv), r_dv))
+
+
+def test_full_pattern_is_dense_attention():
+    w = _small("dense", 700, 128, H=2)
+    q, k, v, do = wl.make_inputs(w, seed=3)
+    qd, kd, vd, dod = (t.to(dev()) for t in (q, k, v, do))
+    pat = spa2.alloc_pattern(w.B, w.H, w.N, dev())
+    spa2.spa2_pattern_full(qd, pat)
+    torch.cuda.synchronize()
+    mask = check_pattern_consistency(pat)
+    assert mask.all()
+    o, lse = gpu_fwd(qd, kd, vd, pat)
+    dq, dk, dv = gpu_bwd(qd, kd, vd, o, dod, lse, pat)
+    for h in range(w.H):
+        r_o, r_lse, _ = orc.attention_definition(f64(q)[0, h], f64(k)[0, h], f64(v)[0, h], mask[0, h])
+        r_dq, r_dk, r_dv = orc.attention_bwd_definition(f64(q)[0, h], f64(k)[0, h], f64(v)[0, h], mask[0, h], f64(do)[0, h])
+        assert_close("O", f64(o)[0, h], r_o)
+        assert_close("dQ", f64(dq)[0, h], r_dq)
+        assert_close("dK", f64(dk)[0, h], r_dk)
+        assert_close("dV", f64(dv)[0, h], r_dv)
+        assert np.abs(f64(lse)[0, h] - r_lse).max() <= 2e-3
+
+
+MASK_CASES = [
+    ("tiny", wl.TINY, 0.25, 0.9),
+    ("ragged-lowrank", _small("rl", 5000, 128, kind="lowrank", H=3), 0.05, 0.8),
+    ("ragged-lowrank-topp-only", _small("rl2", 5000, 128, kind="lowrank", H=2), 0.0, 0.6),
+    ("lowrank-topk-only", _small("rl3", 4096, 64, kind="lowrank", H=2), 0.1, 0.0),
+    ("stress-small", _small("st", 8192, 128, kind="stress", H=2, B=2), 0.05, 0.8),
+    ("wide-row", _small("wide", 20000, 64, kind="lowrank", H=1), 0.03, 0.5),     # Tn = 313 -> 512-wide sort
+    ("very-short", _small("vs", 100, 64, H=1), 0.5, 0.5),
+]
+
+
+@pytest.mark.parametrize("name,w,kf,p", MASK_CASES, ids=[c[0] for c in MASK_CASES])
+def test_mask_protocol(name, w, kf, p):
+    print(f"case {name}: B={w.B} H={w.H} N={w.N} d={w.d} k={kf} p={p}", flush=True)
+    q, k, _, _ = wl.make_inputs(w, seed=4, need_do=False)
+    k_cnt = spa2.spa2_topk_blocks(kf, w.Tn)
+    assert k_cnt == orc.topk_blocks(kf, w.Tn)
+    pat, pbar = gpu_mask(q.to(dev()), k.to(dev()), k_cnt, p)
+    mask = check_pattern_consistency(pat)
+    pbar = pbar.cpu().numpy()
+    assert np.isfinite(pbar).all()
+    tot = dict(stage2_near_cut=0, stage3_hamming=0, stage3_near_cut=0, stage3_ulp_swap=0)
+    for b in range(w.B):
+        for h in range(w.H):
+            ref_pbar = orc.pooled_map(f64(q)[b, h], f64(k)[b, h])
+            r = mask_protocol(mask[b, h], pbar[b, h], ref_pbar, k_cnt, p)
+            assert r["stage1_max_rel"] <= 1e-5, r
+            assert r["stage2_unexplained"] == 0, r
+            assert r["stage3_unexplained"] == 0, r
+            for key in tot:
+                tot[key] += r[key]
+            # invariants of the rule on the GPU mask itself
+            assert (mask[b, h].sum(1) >= max(1, k_cnt)).all()
+            sel_mass = (ref_pbar * mask[b, h]).sum(1)
+            assert ((sel_mass >= np.float32(p) - 1e-5) | mask[b, h].all(1)).all()
+    print("flip counts:", tot, "density:", mask.mean())
+
+
+def test_end_to_end_tiny_mask_then_attention():
+    """The benchmark's small configuration, whole path: mask -> fwd -> bwd."""
+    w = wl.TINY
+    q, k, v, do = wl.make_inputs(w, seed=0)
+    qd, kd, vd, dod = (t.to(dev()) for t in (q, k, v, do))
+    k_cnt = spa2.spa2_topk_blocks(w.k_frac, w.Tn)
+    pat, _ = gpu_mask(qd, kd, k_cnt, w.top_p)
+    mask = check_pattern_consistency(pat)
+    o, lse = gpu_fwd(qd, kd, vd, pat)
+    dq, dk, dv = gpu_bwd(qd, kd, vd, o, dod, lse, pat)
+    # attention parity uses the GPU's mask on both sides, so a boundary flip cannot leak in
+    r_dq, r_dk, r_dv, r_o, r_lse = orc.attention_bwd_bh(f64(q), f64(k), f64(v), mask, f64(do))
+    assert_close("O", f64(o), r_o)
+    assert_close("dQ", f64(dq), r_dq)
+    assert_close("dK", f64(dk), r_dk)
+    assert_close("dV", f64(dv), r_dv)
+    ref_mask, _ = orc.block_mask_bh(f64(q), f64(k), k_cnt, float(np.float32(w.top_p)))
+    print("hamming distance to the fp64 mask:", int((ref_mask != mask).sum()))
+
+
+def test_strided_layout_bnhd():
+    """[B, N, H, d] storage viewed as [B, H, N, d]: same results as the contiguous layout."""
+    w = _small("strided", 600, 128, H=3)
+    q, k, v, do = wl.make_inputs(w, seed=5)
+    mask = _random_mask(w.B, w.H, w.N, 0.5, seed=6)
+    pat = pattern_from_mask(mask, dev())
+
+    def bnhd(t):
+        return t.to(dev()).permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
+
+    qs, ks, vs, dos = bnhd(q), bnhd(k), bnhd(v), bnhd(do)
+    assert not qs.is_contiguous()
+    o = torch.empty_like(qs); lse = torch.empty((w.B, w.H, w.N), dtype=torch.float32, device=dev())
+    spa2.spa2_fwd(qs, ks, vs, pat, 1 / math.sqrt(w.d), o, lse)
+    dq, dk, dv = torch.empty_like(qs), torch.empty_like(qs), torch.empty_like(qs)
+    ws = torch.empty(spa2.spa2_bwd_workspace_bytes(qs), dtype=torch.uint8, device=dev())
+    spa2.spa2_bwd(qs, ks, vs, o, dos, lse, pat, 1 / math.sqrt(w.d), dq, dk, dv, ws)
+    pat2, pbar2 = gpu_mask(qs, ks, 3, 0.5)
+    pat3, pbar3 = gpu_mask(q.to(dev()), k.to(dev()), 3, 0.5)
+    torch.cuda.synchronize()
+    assert torch.equal(pat2.mask, pat3.mask) and torch.equal(pbar2, pbar3)
+    r_dq, r_dk, r_dv, r_o, _ = orc.attention_bwd_bh(f64(q), f64(k), f64(v), mask, f64(do))
+    assert_close("O", f64(o), r_o)
+    assert_close("dQ", f64(dq), r_dq)
+    assert_close("dK", f64(dk), r_dk)
+    assert_close("dV", f64(dv), r_dv)
+
+
+def test_kernels_are_deterministic():
+    w = _small("det", 1500, 128, kind="lowrank", H=2)
+    q, k, v, do = (t.to(dev()) for t in wl.make_inputs(w, seed=7))
+    outs = []
+    for _ in range(2):
+        pat, pbar = gpu_mask(q, k, 3, 0.7)
+        o, lse = gpu_fwd(q, k, v, pat)
+        dq, dk, dv = gpu_bwd(q, k, v, o, do, lse, pat)
+        outs.append((pat.mask, pat.row_idx, pat.col_idx, pbar, o, lse, dq, dk, dv))
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+
+
+def test_error_codes_leave_outputs_untouched():
+    w = _small("err", 256, 128, H=1)
+    q, k, v, do = (t.to(dev()) for t in wl.make_inputs(w, seed=8))
+    pat = spa2.alloc_pattern(1, 1, 256, dev())
+    pat.mask.fill_(9)
+    ws = torch.empty(spa2.spa2_mask_workspace_bytes(q), dtype=torch.uint8, device=dev())
+    with pytest.raises(spa2.Spa2Error) as e:
+        spa2.spa2_mask(q, k, 0, 0.0, 0.1, pat, None, ws)          # both rules off
+    assert e.value.code == -5
+    with pytest.raises(spa2.Spa2Error) as e:
+        spa2.spa2_mask(q, k, 99, 0.5, 0.1, pat, None, ws)         # more blocks than the row has
+    assert e.value.code == -5
+    with pytest.raises(spa2.Spa2Error) as e:
+        spa2.spa2_mask(q, k, 1, 0.5, 0.1, pat, None, ws[:16])     # workspace too small
+    assert e.value.code == -6
+    with pytest.raises(spa2.Spa2Error) as e:
+        spa2.spa2_fwd(q[..., :32], k[..., :32], v[..., :32], pat, 0.1, q[..., :32], torch.empty(256, device=dev()))
+    assert e.value.code == -3                                      # d = 32 unsupported
+    torch.cuda.synchronize()
+    assert (pat.mask == 9).all()
