@@ -101,6 +101,19 @@ int spa2_mask(const void* q, const void* k, const spa2_shape* shape,
               spa2_pattern* out, float* pbar_out,
               void* workspace, size_t workspace_bytes, void* stream);
 
+/* The three stages of spa2_mask, callable one by one (spa2_mask is exactly their sequence):
+ *   spa2_mask_pool     Sec. 2.2 mean pooling: reads Q and K once, leaves the pooled means in `workspace`;
+ *   spa2_mask_select   pooled map, ordering, Top-k UNION Top-p (Sec. 4.1): reads `workspace`, writes
+ *                      mask / row_cnt / row_idx (and pbar_out if given);
+ *   spa2_mask_columns  lists the same pattern per key block: reads out->mask, writes col_cnt / col_idx.
+ * Same argument meaning, ownership and error behaviour as spa2_mask. */
+int spa2_mask_pool(const void* q, const void* k, const spa2_shape* shape,
+                   void* workspace, size_t workspace_bytes, void* stream);
+int spa2_mask_select(const spa2_shape* shape, int32_t topk_blocks, float top_p, float scale,
+                     spa2_pattern* out, float* pbar_out,
+                     void* workspace, size_t workspace_bytes, void* stream);
+int spa2_mask_columns(const spa2_shape* shape, spa2_pattern* out, void* stream);
+
 /* Fills `out` with the all-ones pattern (every tile selected): dense attention
  * through the same kernels, and the sparsity-0 special case. */
 int spa2_pattern_full(const spa2_shape* shape, spa2_pattern* out, void* stream);
@@ -121,6 +134,21 @@ int spa2_fwd(const void* q, const void* k, const void* v, const spa2_shape* shap
 int spa2_bwd(const void* q, const void* k, const void* v, const void* o, const void* d_o,
              const float* lse, const spa2_shape* shape, const spa2_pattern* pattern, float scale,
              void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes, void* stream);
+
+/* The three stages of spa2_bwd, callable one by one (spa2_bwd is exactly their sequence; a caller
+ * that needs only dQ, or only dK and dV, skips the other):
+ *   spa2_bwd_delta  D = rowsum(dO * O), fp32 [B,H,N], left in `workspace`;
+ *   spa2_bwd_dkdv   dK, dV: one pass per key block over the query blocks listed in col_idx;
+ *   spa2_bwd_dq     dQ: one pass per query block over the key blocks listed in row_idx.
+ * dkdv and dq read D from `workspace` (written by spa2_bwd_delta for the same o, d_o). */
+int spa2_bwd_delta(const void* o, const void* d_o, const spa2_shape* shape,
+                   void* workspace, size_t workspace_bytes, void* stream);
+int spa2_bwd_dkdv(const void* q, const void* k, const void* v, const void* d_o, const float* lse,
+                  const spa2_shape* shape, const spa2_pattern* pattern, float scale,
+                  void* dk, void* dv, const void* workspace, size_t workspace_bytes, void* stream);
+int spa2_bwd_dq(const void* q, const void* k, const void* v, const void* d_o, const float* lse,
+                const spa2_shape* shape, const spa2_pattern* pattern, float scale,
+                void* dq, const void* workspace, size_t workspace_bytes, void* stream);
 
 #ifdef __cplusplus
 }

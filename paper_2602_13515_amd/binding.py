@@ -71,12 +71,26 @@ def _load():
     lib.spa2_fwd.argtypes = [vp, vp, vp, shp, pat, f32, vp, vp, vp]
     lib.spa2_bwd.restype = ctypes.c_int
     lib.spa2_bwd.argtypes = [vp, vp, vp, vp, vp, vp, shp, pat, f32, vp, vp, vp, vp, sz, vp]
+    lib.spa2_mask_pool.restype = ctypes.c_int
+    lib.spa2_mask_pool.argtypes = [vp, vp, shp, vp, sz, vp]
+    lib.spa2_mask_select.restype = ctypes.c_int
+    lib.spa2_mask_select.argtypes = [shp, i32, f32, f32, pat, vp, vp, sz, vp]
+    lib.spa2_mask_columns.restype = ctypes.c_int
+    lib.spa2_mask_columns.argtypes = [shp, pat, vp]
+    lib.spa2_bwd_delta.restype = ctypes.c_int
+    lib.spa2_bwd_delta.argtypes = [vp, vp, shp, vp, sz, vp]
+    lib.spa2_bwd_dkdv.restype = ctypes.c_int
+    lib.spa2_bwd_dkdv.argtypes = [vp, vp, vp, vp, vp, shp, pat, f32, vp, vp, vp, sz, vp]
+    lib.spa2_bwd_dq.restype = ctypes.c_int
+    lib.spa2_bwd_dq.argtypes = [vp, vp, vp, vp, vp, shp, pat, f32, vp, vp, sz, vp]
     _lib = lib
     return lib
 
 
 EXPORTED_SYMBOLS = ("spa2_version", "spa2_strerror", "spa2_topk_blocks", "spa2_mask_workspace_bytes",
-                    "spa2_bwd_workspace_bytes", "spa2_mask", "spa2_pattern_full", "spa2_fwd", "spa2_bwd")
+                    "spa2_bwd_workspace_bytes", "spa2_mask", "spa2_mask_pool", "spa2_mask_select",
+                    "spa2_mask_columns", "spa2_pattern_full", "spa2_fwd", "spa2_bwd", "spa2_bwd_delta",
+                    "spa2_bwd_dkdv", "spa2_bwd_dq")
 
 
 # ------------------------------------------------------------------ plumbing (memory only)
@@ -193,3 +207,55 @@ def spa2_bwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, o: torch.Tensor,
                           dv.data_ptr(), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                           _stream(q))
     _check(rc, "spa2_bwd")
+
+
+# ------------------------------------------------------------------ the stages of spa2_mask / spa2_bwd, one by one
+def _nbytes(t: torch.Tensor) -> int:
+    return t.numel() * t.element_size()
+
+
+def spa2_mask_pool(q: torch.Tensor, k: torch.Tensor, workspace: torch.Tensor) -> None:
+    _same_layout(q, k)
+    shape = _shape_of(q)
+    _check(_load().spa2_mask_pool(q.data_ptr(), k.data_ptr(), ctypes.byref(shape), workspace.data_ptr(),
+                                  _nbytes(workspace), _stream(q)), "spa2_mask_pool")
+
+
+def spa2_mask_select(like: torch.Tensor, topk_blocks: int, top_p: float, scale: float, out: Pattern,
+                     pbar_out: Optional[torch.Tensor], workspace: torch.Tensor) -> None:
+    shape = _shape_of(like)
+    pat = out._c()
+    _check(_load().spa2_mask_select(ctypes.byref(shape), int(topk_blocks), float(top_p), float(scale),
+                                    ctypes.byref(pat), pbar_out.data_ptr() if pbar_out is not None else None,
+                                    workspace.data_ptr(), _nbytes(workspace), _stream(like)), "spa2_mask_select")
+
+
+def spa2_mask_columns(like: torch.Tensor, out: Pattern) -> None:
+    shape = _shape_of(like)
+    pat = out._c()
+    _check(_load().spa2_mask_columns(ctypes.byref(shape), ctypes.byref(pat), _stream(like)), "spa2_mask_columns")
+
+
+def spa2_bwd_delta(o: torch.Tensor, d_o: torch.Tensor, workspace: torch.Tensor) -> None:
+    _same_layout(o, d_o)
+    shape = _shape_of(o)
+    _check(_load().spa2_bwd_delta(o.data_ptr(), d_o.data_ptr(), ctypes.byref(shape), workspace.data_ptr(),
+                                  _nbytes(workspace), _stream(o)), "spa2_bwd_delta")
+
+
+def spa2_bwd_dkdv(q, k, v, d_o, lse, pattern: Pattern, scale: float, dk, dv, workspace) -> None:
+    _same_layout(q, k, v, d_o, dk, dv)
+    shape = _shape_of(q)
+    pat = pattern._c()
+    _check(_load().spa2_bwd_dkdv(q.data_ptr(), k.data_ptr(), v.data_ptr(), d_o.data_ptr(), lse.data_ptr(),
+                                 ctypes.byref(shape), ctypes.byref(pat), float(scale), dk.data_ptr(), dv.data_ptr(),
+                                 workspace.data_ptr(), _nbytes(workspace), _stream(q)), "spa2_bwd_dkdv")
+
+
+def spa2_bwd_dq(q, k, v, d_o, lse, pattern: Pattern, scale: float, dq, workspace) -> None:
+    _same_layout(q, k, v, d_o, dq)
+    shape = _shape_of(q)
+    pat = pattern._c()
+    _check(_load().spa2_bwd_dq(q.data_ptr(), k.data_ptr(), v.data_ptr(), d_o.data_ptr(), lse.data_ptr(),
+                               ctypes.byref(shape), ctypes.byref(pat), float(scale), dq.data_ptr(),
+                               workspace.data_ptr(), _nbytes(workspace), _stream(q)), "spa2_bwd_dq")

@@ -32,6 +32,8 @@ MaskWs mask_ws(const Dims& m) {
   return w;
 }
 
+size_t bwd_ws_bytes(const Dims& m) { return round256((size_t)m.B * m.H * m.N * sizeof(float)); }
+
 }  // namespace
 
 extern "C" {
@@ -67,13 +69,57 @@ size_t spa2_mask_workspace_bytes(const spa2_shape* shape) {
 
 size_t spa2_bwd_workspace_bytes(const spa2_shape* shape) {
   if (check_shape(shape) != SPA2_OK) return 0;
+  return bwd_ws_bytes(make_dims(*shape));
+}
+
+int spa2_mask_pool(const void* q, const void* k, const spa2_shape* shape, void* workspace,
+                   size_t workspace_bytes, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != SPA2_OK) return rc;
+  if (!q || !k) return SPA2_ERR_NULL;
+  if (!aligned16(q) || !aligned16(k)) return SPA2_ERR_ALIGN;
   const Dims m = make_dims(*shape);
-  return round256((size_t)m.B * m.H * m.N * sizeof(float));
+  const MaskWs w = mask_ws(m);
+  if (!workspace || workspace_bytes < w.total) return SPA2_ERR_WORKSPACE;
+  if (!aligned16(workspace)) return SPA2_ERR_ALIGN;
+  float* qbar = (float*)((char*)workspace + w.qbar);
+  float* kbar = (float*)((char*)workspace + w.kbar);
+  return launch_pool(q, k, m, qbar, kbar, (hipStream_t)stream) == hipSuccess ? SPA2_OK : SPA2_ERR_LAUNCH;
+}
+
+int spa2_mask_select(const spa2_shape* shape, int32_t topk_blocks, float top_p, float scale, spa2_pattern* out,
+                     float* pbar_out, void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != SPA2_OK) return rc;
+  if (!out || !out->mask || !out->row_cnt || !out->row_idx) return SPA2_ERR_NULL;
+  const Dims m = make_dims(*shape);
+  if (m.Tn > SPA2_MAX_TN) return SPA2_ERR_SHAPE;
+  if (topk_blocks < 0 || topk_blocks > m.Tn) return SPA2_ERR_RANGE;
+  if (!(top_p >= 0.f) || !(top_p <= 1.f)) return SPA2_ERR_RANGE;
+  if (topk_blocks == 0 && top_p == 0.f) return SPA2_ERR_RANGE;
+  if (!(scale > 0.f) || !isfinite(scale)) return SPA2_ERR_RANGE;
+  const MaskWs w = mask_ws(m);
+  if (!workspace || workspace_bytes < w.total) return SPA2_ERR_WORKSPACE;
+  if (!aligned16(workspace)) return SPA2_ERR_ALIGN;
+  const float* qbar = (const float*)((char*)workspace + w.qbar);
+  const float* kbar = (const float*)((char*)workspace + w.kbar);
+  return launch_select(qbar, kbar, m, topk_blocks, top_p, scale, out->mask, out->row_cnt, out->row_idx, pbar_out,
+                       (hipStream_t)stream) == hipSuccess ? SPA2_OK : SPA2_ERR_LAUNCH;
+}
+
+int spa2_mask_columns(const spa2_shape* shape, spa2_pattern* out, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != SPA2_OK) return rc;
+  if (!out || !out->mask || !out->col_cnt || !out->col_idx) return SPA2_ERR_NULL;
+  const Dims m = make_dims(*shape);
+  return launch_columns(out->mask, m, out->col_cnt, out->col_idx, (hipStream_t)stream) == hipSuccess
+             ? SPA2_OK : SPA2_ERR_LAUNCH;
 }
 
 int spa2_mask(const void* q, const void* k, const spa2_shape* shape, int32_t topk_blocks, float top_p,
               float scale, spa2_pattern* out, float* pbar_out, void* workspace, size_t workspace_bytes,
               void* stream) {
+  // validate everything first, so that a rejected call has launched nothing
   int rc = check_shape(shape);
   if (rc != SPA2_OK) return rc;
   if (!q || !k || !out || !out->mask || !out->row_cnt || !out->row_idx) return SPA2_ERR_NULL;
@@ -85,20 +131,14 @@ int spa2_mask(const void* q, const void* k, const spa2_shape* shape, int32_t top
   if (!(top_p >= 0.f) || !(top_p <= 1.f)) return SPA2_ERR_RANGE;
   if (topk_blocks == 0 && top_p == 0.f) return SPA2_ERR_RANGE;
   if (!(scale > 0.f) || !isfinite(scale)) return SPA2_ERR_RANGE;
-  const MaskWs w = mask_ws(m);
-  if (!workspace || workspace_bytes < w.total) return SPA2_ERR_WORKSPACE;
+  if (!workspace || workspace_bytes < mask_ws(m).total) return SPA2_ERR_WORKSPACE;
   if (!aligned16(workspace)) return SPA2_ERR_ALIGN;
-  hipStream_t st = (hipStream_t)stream;
-  float* qbar = (float*)((char*)workspace + w.qbar);
-  float* kbar = (float*)((char*)workspace + w.kbar);
-  if (launch_pool(q, k, m, qbar, kbar, st) != hipSuccess) return SPA2_ERR_LAUNCH;
-  if (launch_select(qbar, kbar, m, topk_blocks, top_p, scale, out->mask, out->row_cnt, out->row_idx, pbar_out,
-                    st) != hipSuccess)
-    return SPA2_ERR_LAUNCH;
-  if (out->col_cnt &&
-      launch_columns(out->mask, m, out->col_cnt, out->col_idx, st) != hipSuccess)
-    return SPA2_ERR_LAUNCH;
-  return SPA2_OK;
+  rc = spa2_mask_pool(q, k, shape, workspace, workspace_bytes, stream);
+  if (rc != SPA2_OK) return rc;
+  rc = spa2_mask_select(shape, topk_blocks, top_p, scale, out, pbar_out, workspace, workspace_bytes, stream);
+  if (rc != SPA2_OK) return rc;
+  if (out->col_cnt) rc = spa2_mask_columns(shape, out, stream);
+  return rc;
 }
 
 int spa2_pattern_full(const spa2_shape* shape, spa2_pattern* out, void* stream) {
@@ -126,6 +166,52 @@ int spa2_fwd(const void* q, const void* k, const void* v, const spa2_shape* shap
   return SPA2_OK;
 }
 
+int spa2_bwd_delta(const void* o, const void* d_o, const spa2_shape* shape, void* workspace,
+                   size_t workspace_bytes, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != SPA2_OK) return rc;
+  if (!o || !d_o) return SPA2_ERR_NULL;
+  if (!aligned16(o) || !aligned16(d_o)) return SPA2_ERR_ALIGN;
+  const Dims m = make_dims(*shape);
+  if (!workspace || workspace_bytes < bwd_ws_bytes(m)) return SPA2_ERR_WORKSPACE;
+  if (!aligned16(workspace)) return SPA2_ERR_ALIGN;
+  return launch_bwd_delta(o, d_o, m, (float*)workspace, (hipStream_t)stream) == hipSuccess ? SPA2_OK
+                                                                                           : SPA2_ERR_LAUNCH;
+}
+
+int spa2_bwd_dkdv(const void* q, const void* k, const void* v, const void* d_o, const float* lse,
+                  const spa2_shape* shape, const spa2_pattern* pattern, float scale, void* dk, void* dv,
+                  const void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != SPA2_OK) return rc;
+  if (!q || !k || !v || !d_o || !lse || !dk || !dv || !pattern || !pattern->col_cnt || !pattern->col_idx)
+    return SPA2_ERR_NULL;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(d_o) || !aligned16(dk) || !aligned16(dv))
+    return SPA2_ERR_ALIGN;
+  if (!(scale > 0.f) || !isfinite(scale)) return SPA2_ERR_RANGE;
+  const Dims m = make_dims(*shape);
+  if (!workspace || workspace_bytes < bwd_ws_bytes(m)) return SPA2_ERR_WORKSPACE;
+  if (!aligned16(workspace)) return SPA2_ERR_ALIGN;
+  return launch_bwd_dkdv(q, k, v, d_o, lse, (const float*)workspace, m, pattern->col_cnt, pattern->col_idx, scale,
+                         dk, dv, (hipStream_t)stream) == hipSuccess ? SPA2_OK : SPA2_ERR_LAUNCH;
+}
+
+int spa2_bwd_dq(const void* q, const void* k, const void* v, const void* d_o, const float* lse,
+                const spa2_shape* shape, const spa2_pattern* pattern, float scale, void* dq,
+                const void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != SPA2_OK) return rc;
+  if (!q || !k || !v || !d_o || !lse || !dq || !pattern || !pattern->row_cnt || !pattern->row_idx)
+    return SPA2_ERR_NULL;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(d_o) || !aligned16(dq)) return SPA2_ERR_ALIGN;
+  if (!(scale > 0.f) || !isfinite(scale)) return SPA2_ERR_RANGE;
+  const Dims m = make_dims(*shape);
+  if (!workspace || workspace_bytes < bwd_ws_bytes(m)) return SPA2_ERR_WORKSPACE;
+  if (!aligned16(workspace)) return SPA2_ERR_ALIGN;
+  return launch_bwd_dq(q, k, v, d_o, lse, (const float*)workspace, m, pattern->row_cnt, pattern->row_idx, scale,
+                       dq, (hipStream_t)stream) == hipSuccess ? SPA2_OK : SPA2_ERR_LAUNCH;
+}
+
 int spa2_bwd(const void* q, const void* k, const void* v, const void* o, const void* d_o, const float* lse,
              const spa2_shape* shape, const spa2_pattern* pattern, float scale, void* dq, void* dk, void* dv,
              void* workspace, size_t workspace_bytes, void* stream) {
@@ -138,18 +224,13 @@ int spa2_bwd(const void* q, const void* k, const void* v, const void* o, const v
     return SPA2_ERR_ALIGN;
   if (!(scale > 0.f) || !isfinite(scale)) return SPA2_ERR_RANGE;
   const Dims m = make_dims(*shape);
-  const size_t need = round256((size_t)m.B * m.H * m.N * sizeof(float));
-  if (!workspace || workspace_bytes < need) return SPA2_ERR_WORKSPACE;
+  if (!workspace || workspace_bytes < bwd_ws_bytes(m)) return SPA2_ERR_WORKSPACE;
   if (!aligned16(workspace)) return SPA2_ERR_ALIGN;
-  hipStream_t st = (hipStream_t)stream;
-  float* delta = (float*)workspace;
-  if (launch_bwd_delta(o, d_o, m, delta, st) != hipSuccess) return SPA2_ERR_LAUNCH;
-  if (launch_bwd_dkdv(q, k, v, d_o, lse, delta, m, pattern->col_cnt, pattern->col_idx, scale, dk, dv, st) !=
-      hipSuccess)
-    return SPA2_ERR_LAUNCH;
-  if (launch_bwd_dq(q, k, v, d_o, lse, delta, m, pattern->row_cnt, pattern->row_idx, scale, dq, st) != hipSuccess)
-    return SPA2_ERR_LAUNCH;
-  return SPA2_OK;
+  rc = spa2_bwd_delta(o, d_o, shape, workspace, workspace_bytes, stream);
+  if (rc != SPA2_OK) return rc;
+  rc = spa2_bwd_dkdv(q, k, v, d_o, lse, shape, pattern, scale, dk, dv, workspace, workspace_bytes, stream);
+  if (rc != SPA2_OK) return rc;
+  return spa2_bwd_dq(q, k, v, d_o, lse, shape, pattern, scale, dq, workspace, workspace_bytes, stream);
 }
 
 }  // extern "C"

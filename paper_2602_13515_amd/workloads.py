@@ -84,8 +84,10 @@ def head_inputs(w: Workload, b: int, h: int, seed: int = 0, device="cpu",
     do = _randn((N, d), g, device) if need_do else None
     if w.kind == "lowrank":
         rank, chunk = 4, 64
-        basis, _ = torch.linalg.qr(_randn((d, rank), g, device))      # [d, rank], orthonormal columns
-        u = basis.T.contiguous() * (d ** 0.25)                          # [rank, d]
+        # the small basis is always drawn and orthonormalised on the CPU (no device linear algebra needed)
+        gc = _gen("cpu", seed * 1_000_003 + (b * w.H + h) * 7919 + 18)
+        basis, _ = torch.linalg.qr(_randn((d, rank), gc, "cpu"))       # [d, rank], orthonormal columns
+        u = (basis.T.contiguous() * (d ** 0.25)).to(device)             # [rank, d]
         n_chunks = -(-N // chunk)
         cq = _randn((n_chunks, rank), g, device)
         ck = _randn((n_chunks, rank), g, device)
