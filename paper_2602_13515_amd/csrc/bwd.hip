@@ -70,9 +70,8 @@ struct DqArgs {
 
 template <int D>
 struct DqCfg {
-  static constexpr int KP = D + 8;     // K tile pitch (row reads for S^T, transposing reads for dQ^T)
-  static constexpr int VP = D + 8;     // V tile pitch (row reads for dP^T)
-  static constexpr int K_ELEMS = BKV * KP;
+  static constexpr int K_ELEMS = BKV * D;      // K tile, XOR-swizzled: read along rows (S^T) and transposed (dQ^T)
+  static constexpr int VP = D + 8;             // V tile pitch (row reads for dP^T)
   static constexpr int V_ELEMS = BKV * VP;
   static constexpr int CH = BKV * D / 8 / 256;
 };
@@ -96,8 +95,17 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(DqArgs a) {
   const int N = a.N;
   const int cnt = min(max(a.row_cnt[(int64_t)bh * a.Tm + i], 0), a.Tn);   // clamped: see fwd.hip
   const int32_t* idx = a.row_idx + ((int64_t)bh * a.Tm + i) * a.Tn;
-
   const int qrow = i * BQ + w * 32 + r32;
+
+  if (cnt == 0) {
+    if (qrow < N) {
+      uint16_t* op = a.dq + base + (int64_t)qrow * a.sn + (D / 2) * hf;
+#pragma unroll
+      for (int c = 0; c < D / 16; ++c) *(u32x4*)(op + 8 * c) = u32x4{0, 0, 0, 0};
+    }
+    return;
+  }
+
   const int qrow_ld = qrow < N ? qrow : N - 1;
   bf16x8 qf[D / 16], dof[D / 16];
   {
@@ -111,31 +119,40 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(DqArgs a) {
   const float lse2 = a.lse[(int64_t)bh * N + qrow_ld] * LOG2E;
   const float dlt = a.delta[(int64_t)bh * N + qrow_ld];
 
+  // K/V tile staging: same scheme as the forward kernel (rows past N clamped; their P is zero)
+  constexpr int RSTEP = 256 / (D / 8);
+  const int ld_row = tid / (D / 8), ld_col = (tid % (D / 8)) * 8;
+  uint32_t goff[C::CH];
+#pragma unroll
+  for (int r = 0; r < C::CH; ++r) goff[r] = (uint32_t)(((ld_row + RSTEP * r) * a.sn + ld_col) * 2);
+  const int lds_k = swz_idx<D>(ld_row, ld_col), lds_v = ld_row * C::VP + ld_col;   // RSTEP is a multiple of 16 rows
   u32x4 kreg[C::CH], vreg[C::CH];
   auto load_tile = [&](int j) {
     j = min(max(j, 0), a.Tn - 1);
+    const int64_t tile = (base + (int64_t)j * BKV * a.sn) * 2;
+    const char* kp = (const char*)a.k + tile;
+    const char* vp = (const char*)a.v + tile;
+    if ((j + 1) * BKV <= N) {
 #pragma unroll
-    for (int r = 0; r < C::CH; ++r) {
-      const int c = tid + 256 * r;
-      const int row = c / (D / 8), col = (c % (D / 8)) * 8;
-      const int tok = j * BKV + row;
-      if (tok < N) {
-        const int64_t off = base + (int64_t)tok * a.sn + col;
-        kreg[r] = *(const u32x4*)(a.k + off);
-        vreg[r] = *(const u32x4*)(a.v + off);
-      } else {
-        kreg[r] = u32x4{0, 0, 0, 0};
-        vreg[r] = u32x4{0, 0, 0, 0};
+      for (int r = 0; r < C::CH; ++r) {
+        kreg[r] = *(const u32x4*)(kp + goff[r]);
+        vreg[r] = *(const u32x4*)(vp + goff[r]);
+      }
+    } else {
+      const int last = N - 1 - j * BKV;
+#pragma unroll
+      for (int r = 0; r < C::CH; ++r) {
+        const uint32_t o2 = (uint32_t)((min(ld_row + RSTEP * r, last) * a.sn + ld_col) * 2);
+        kreg[r] = *(const u32x4*)(kp + o2);
+        vreg[r] = *(const u32x4*)(vp + o2);
       }
     }
   };
   auto store_tile = [&](int buf) {
 #pragma unroll
     for (int r = 0; r < C::CH; ++r) {
-      const int c = tid + 256 * r;
-      const int row = c / (D / 8), col = (c % (D / 8)) * 8;
-      *(u32x4*)(Ks + buf * C::K_ELEMS + row * C::KP + col) = kreg[r];
-      *(u32x4*)(Vs + buf * C::V_ELEMS + row * C::VP + col) = vreg[r];
+      *(u32x4*)(Ks + buf * C::K_ELEMS + lds_k + RSTEP * r * D) = kreg[r];
+      *(u32x4*)(Vs + buf * C::V_ELEMS + lds_v + RSTEP * r * C::VP) = vreg[r];
     }
   };
 
@@ -145,15 +162,22 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(DqArgs a) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[mb][v] = 0.f;
 
-  const int k_off = r32 * C::KP + 8 * hf;
+  // per-lane LDS offsets.  K row reads: row 32kb + r32, logical chunk 2kk + hf.
+  int k_off[D / 16];
+#pragma unroll
+  for (int kk = 0; kk < D / 16; ++kk) k_off[kk] = swz_idx<D>(r32, 16 * kk + 8 * hf);
   const int v_off = r32 * C::VP + 8 * hf;
-  const int s16 = lane & 15, blk16 = lane >> 4;
-  const int kt_off = (4 * hf + (s16 >> 2)) * C::KP + 16 * (blk16 & 1) + 4 * (s16 & 3);
+  // K transposing reads: rows (16-row group) + 8*which + 4hf + (s16>>2), columns 32mb + 16hb + 4(s16&3)
+  const int s16 = lane & 15, hb16 = (lane >> 4) & 1;
+  int kt_off[2][D / 32];
+#pragma unroll
+  for (int wh = 0; wh < 2; ++wh)
+#pragma unroll
+    for (int mb = 0; mb < D / 32; ++mb)
+      kt_off[wh][mb] = swz_idx<D>(8 * wh + 4 * hf + (s16 >> 2), 32 * mb + 16 * hb16 + 4 * (s16 & 3));
 
-  if (cnt > 0) {
-    load_tile(idx[0]);
-    store_tile(0);
-  }
+  load_tile(idx[0]);
+  store_tile(0);
   __syncthreads();
 
   for (int t = 0; t < cnt; ++t) {
@@ -170,7 +194,7 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(DqArgs a) {
       for (int v = 0; v < 16; ++v) { s[kb][v] = 0.f; dp[kb][v] = 0.f; }
 #pragma unroll
       for (int kk = 0; kk < D / 16; ++kk) {
-        const bf16x8 ka = *(const bf16x8*)(Kb + k_off + kb * 32 * C::KP + 16 * kk);
+        const bf16x8 ka = *(const bf16x8*)(Kb + k_off[kk] + kb * 32 * D);
         s[kb] = mfma32(ka, qf[kk], s[kb]);
       }
 #pragma unroll
@@ -180,27 +204,34 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(DqArgs a) {
       }
     }
     const bool tail = (j + 1) * BKV > N;
+    uint32_t dsk[2][8];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        float p = fast_exp2(fmaf(s[kb][v], a.scale_log2, -lse2));
-        if (tail) {
-          const int key = j * BKV + kb * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
-          if (key >= N) p = 0.f;
+      for (int u = 0; u < 8; ++u) {
+        float ds2[2];
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          const int v = 2 * u + e;
+          float p = fast_exp2(fmaf(s[kb][v], a.scale_log2, -lse2));
+          if (tail) {
+            const int key = j * BKV + kb * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
+            if (key >= N) p = 0.f;
+          }
+          ds2[e] = p * (dp[kb][v] - dlt);     // dS^T
         }
-        s[kb][v] = p * (dp[kb][v] - dlt);     // dS^T
+        dsk[kb][u] = pack_bf16(ds2[0], ds2[1]);
       }
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int cc = 0; cc < 2; ++cc) {
-        const bf16x8 dsb = make_bf16x8(s[kb][8 * cc + 0], s[kb][8 * cc + 1], s[kb][8 * cc + 2], s[kb][8 * cc + 3],
-                                       s[kb][8 * cc + 4], s[kb][8 * cc + 5], s[kb][8 * cc + 6], s[kb][8 * cc + 7]);
-        const uint16_t* krow = Kb + kt_off + (32 * kb + 16 * cc) * C::KP;
+        const u32x4 du = {dsk[kb][4 * cc], dsk[kb][4 * cc + 1], dsk[kb][4 * cc + 2], dsk[kb][4 * cc + 3]};
+        const bf16x8 dsb = __builtin_bit_cast(bf16x8, du);
+        const uint16_t* krow = Kb + (32 * kb + 16 * cc) * D;
 #pragma unroll
         for (int mb = 0; mb < D / 32; ++mb) {
-          const bf16x8 kta = join_tr(lds_read_tr4(krow + 32 * mb), lds_read_tr4(krow + 8 * C::KP + 32 * mb));
+          const bf16x8 kta = join_tr(lds_read_tr4(krow + kt_off[0][mb]), lds_read_tr4(krow + kt_off[1][mb]));
           acc[mb] = mfma32(kta, dsb, acc[mb]);
         }
       }
@@ -247,138 +278,207 @@ struct DkvArgs {
   float scale, scale_log2;
 };
 
-template <int D>
-struct DkvCfg {
-  static constexpr int QP = D + 8;                // Q / dO tile pitch
-  static constexpr int T_ELEMS = BQ * QP;
-  static constexpr int CH = BQ * D / 8 / 256;     // 16-byte chunks per thread per 128-row tile
-};
+typedef __attribute__((address_space(1))) const void gptr_t;
+typedef __attribute__((address_space(3))) void lptr_t;
 
-// One workgroup per key block j (64 keys); wave w owns keys 16w..16w+15 and keeps its
-// K and V rows in registers.  For every query block i that selected j (128 queries,
-// staged in LDS together with dO, LSE and D):
-//   S  (q x keys) = Q_i K_j^T        16x16x32 MFMA, A = Q rows from LDS, B = K^T in registers
-//   dP (q x keys) = dO_i V_j^T       same with dO and V
-//   P = exp(S - LSE), dS = P * (dP - D)     accumulator layout: lane = key, registers = queries
-//   dV^T (d x keys) += dO_i^T P      A = dO^T via transposing LDS reads, B = P from registers
-//   dK^T (d x keys) += Q_i^T dS      A = Q^T  via transposing LDS reads, B = dS from registers
+// One workgroup (8 waves) per key block j (64 keys).  Wave (wq, wk) owns the 32 queries 32wq.. of the
+// current query block and the 32 keys 32wk.. of the key block; it keeps its K^T / V^T fragments and its
+// dK^T / dV^T accumulators (d x 32 keys each) in registers for the whole kernel.  For every query block i
+// that selected j, Q_i and dO_i (128 x d) are copied global -> LDS directly (no register staging),
+// XOR-swizzled so that both read patterns are conflict-free, double-buffered one tile ahead:
+//   S  (q x keys) = Q_i K_j^T        A = Q rows from LDS,  B = K^T fragments (registers)
+//   dP (q x keys) = dO_i V_j^T       A = dO rows from LDS, B = V^T fragments (registers)
+//   P = exp(S - LSE), dS = P * (dP - D)      accumulator layout: lane = key, registers = queries
+//   dV^T (d x keys) += dO_i^T P      A = dO^T through transposing LDS reads, B = P  (registers)
+//   dK^T (d x keys) += Q_i^T dS      A = Q^T  through transposing LDS reads, B = dS (registers)
+// Every MFMA (32x32x16) has exactly one operand from LDS.  The four waves that share a key half add
+// their partial sums through LDS at the end.
 template <int D>
-__global__ __launch_bounds__(256, 2) void dkdv_kernel(DkvArgs a) {
-  using C = DkvCfg<D>;
-  __shared__ __align__(16) uint16_t Qs[C::T_ELEMS];
-  __shared__ __align__(16) uint16_t Os[C::T_ELEMS];
-  __shared__ __align__(16) float lse_s[BQ];
-  __shared__ __align__(16) float dlt_s[BQ];
+__global__ __launch_bounds__(512, 2) void dkdv_kernel(DkvArgs a) {
+  constexpr int TILE = BQ * D;                       // elements of one 128-row tile
+  constexpr int CPR = D / 8;                         // 16-byte chunks per row
+  constexpr int CH = BQ * CPR / 512;                 // chunks per thread per tile
+  __shared__ __align__(16) uint16_t smem[4 * TILE];  // stage s: Q tile at 2s*TILE, dO tile at (2s+1)*TILE
+  __shared__ __align__(16) float lse_s[2 * BQ];
+  __shared__ __align__(16) float dlt_s[2 * BQ];
 
-  const HeadBlock hb = xcd_map(blockIdx.x, a.Tn, a.chunk);
-  if (!hb.valid) return;
-  const int bh = hb.bh, j = hb.blk;
+  const HeadBlock hbk = xcd_map(blockIdx.x, a.Tn, a.chunk);
+  if (!hbk.valid) return;
+  const int bh = hbk.bh, j = hbk.blk;
   const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int r16 = lane & 15, G = lane >> 4;
+  const int wq = w & 3, wk = w >> 2;
+  const int r32 = lane & 31, hf = lane >> 5;
   const int N = a.N;
   const int cnt = min(max(a.col_cnt[(int64_t)bh * a.Tn + j], 0), a.Tm);   // clamped: see fwd.hip
   const int32_t* idx = a.col_idx + ((int64_t)bh * a.Tn + j) * a.Tm;
 
-  // K^T / V^T fragments (B operands): lane = key, 8 consecutive channels per 32-wide k step
-  const int key = j * BKV + w * 16 + r16;
+  const int key = j * BKV + wk * 32 + r32;
   const bool key_ok = key < N;
-  bf16x8 kf[D / 32], vf[D / 32];
-  {
-    const int64_t off = base + (int64_t)(key_ok ? key : N - 1) * a.sn + 8 * G;
+
+  if (cnt == 0) {   // no query block selected this key block: zero gradients
+    if (key_ok && wq == 0) {
+      const int64_t out_off = base + (int64_t)key * a.sn + 4 * hf;
 #pragma unroll
-    for (int kk = 0; kk < D / 32; ++kk) {
-      kf[kk] = *(const bf16x8*)(a.k + off + 32 * kk);
-      vf[kk] = *(const bf16x8*)(a.v + off + 32 * kk);
+      for (int c = 0; c < D / 8; ++c) {
+        *(u32x2*)(a.dk + out_off + 8 * c) = u32x2{0, 0};
+        *(u32x2*)(a.dv + out_off + 8 * c) = u32x2{0, 0};
+      }
+    }
+    return;
+  }
+
+  // K^T / V^T fragments (B operands): lane = key, 8 consecutive channels per 16-wide k step
+  bf16x8 kf[D / 16], vf[D / 16];
+  {
+    const int64_t off = base + (int64_t)(key_ok ? key : N - 1) * a.sn + 8 * hf;
+#pragma unroll
+    for (int kk = 0; kk < D / 16; ++kk) {
+      kf[kk] = *(const bf16x8*)(a.k + off + 16 * kk);
+      vf[kk] = *(const bf16x8*)(a.v + off + 16 * kk);
     }
   }
 
-  f32x4 dk_acc[D / 16], dv_acc[D / 16];
+  f32x16 dk_acc[D / 32], dv_acc[D / 32];
 #pragma unroll
-  for (int nb = 0; nb < D / 16; ++nb) {
-    dk_acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
-    dv_acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
-  }
+  for (int mb = 0; mb < D / 32; ++mb)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { dk_acc[mb][v] = 0.f; dv_acc[mb][v] = 0.f; }
 
-  const int a_off = r16 * C::QP + 8 * G;                                        // row reads (A operand)
-  const int t_off = (4 * G + (r16 >> 2)) * C::QP + 4 * (r16 & 3);               // transposing reads
+  // global -> LDS copy of one query block.  The destination of a wave-wide 16-byte-per-lane copy is
+  // linear (wave base + 16 * lane), so the swizzle is applied on the source side: the lane that fills
+  // chunk position pc of row `row` fetches logical chunk pc ^ swz(row).  Rows past N are clamped to the
+  // last token and get LSE = +inf, so their P and dS are exactly zero.
+  // thread t fills chunk position t % CPR of rows t / CPR + r * (512 / CPR); 512 / CPR is a multiple of
+  // 16 rows, so the swizzle term is the same for every r
+  // (recomputed per request from the thread id: a few integer ops instead of two live registers)
+  float stat = 0.f;                                    // LSE (threads 0..127) or D (threads 128..255) of one row
+  auto request_tile = [&](int i, int stage) {
+    i = min(max(i, 0), a.Tm - 1);
+    const int64_t tile = base + (int64_t)i * BQ * a.sn;
+    const int last = min(BQ - 1, N - 1 - i * BQ);
+    const int ld_row0 = tid / CPR;
+    const int ld_c8 = ((tid % CPR) ^ swz<D>(ld_row0)) * 8;
+#pragma unroll
+    for (int r = 0; r < CH; ++r) {
+      const int64_t off = tile + (int64_t)min(ld_row0 + r * (512 / CPR), last) * a.sn + ld_c8;
+      uint16_t* dst = smem + 2 * stage * TILE + (r * 512 + w * 64) * 8;       // wave-uniform
+      __builtin_amdgcn_global_load_lds((gptr_t*)(a.q + off), (lptr_t*)dst, 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t*)(a.d_o + off), (lptr_t*)(dst + TILE), 16, 0, 0);
+    }
+    if (tid < 2 * BQ) {
+      const int srow = i * BQ + (tid & (BQ - 1));
+      if (srow < N) stat = tid < BQ ? a.lse[(int64_t)bh * N + srow] * LOG2E : a.delta[(int64_t)bh * N + srow];
+      else          stat = tid < BQ ? INFINITY : 0.f;
+    }
+  };
+  auto publish_stat = [&](int stage) {
+    if (tid < BQ) lse_s[stage * BQ + tid] = stat;
+    else if (tid < 2 * BQ) dlt_s[stage * BQ + tid - BQ] = stat;
+  };
+
+  // per-lane LDS element offsets inside a tile.  Row reads: row 32wq + r32, logical chunk 2kk + hf; the
+  // chunk field of the element index is XORed with the compile-time part (kk << 4).
+  int a_base = swz_idx<D>(wq * 32 + r32, 8 * hf);
+  // transposing reads: row 32wq + 16c + 8*which + 4hf + (s16>>2), columns 32mb + 16hb + 4(s16&3);
+  // the part that depends on mb is XORed in (mb << 5)
+  const int s16 = lane & 15, hb16 = (lane >> 4) & 1;
+  int t_base0 = swz_idx<D>(wq * 32 + 4 * hf + (s16 >> 2), 16 * hb16 + 4 * (s16 & 3));
+  int t_base1 = swz_idx<D>(wq * 32 + 8 + 4 * hf + (s16 >> 2), 16 * hb16 + 4 * (s16 & 3));
+
+  request_tile(idx[0], 0);
+  publish_stat(0);
+  __syncthreads();
 
   for (int t = 0; t < cnt; ++t) {
-    const int i = min(max(idx[t], 0), a.Tm - 1);
-    __syncthreads();                       // previous tile fully consumed
-#pragma unroll
-    for (int r = 0; r < C::CH; ++r) {
-      const int c = tid + 256 * r;
-      const int row = c / (D / 8), col = (c % (D / 8)) * 8;
-      const int tok = i * BQ + row;
-      u32x4 qv = u32x4{0, 0, 0, 0}, ov = u32x4{0, 0, 0, 0};
-      if (tok < N) {
-        const int64_t off = base + (int64_t)tok * a.sn + col;
-        qv = *(const u32x4*)(a.q + off);
-        ov = *(const u32x4*)(a.d_o + off);
-      }
-      *(u32x4*)(Qs + row * C::QP + col) = qv;
-      *(u32x4*)(Os + row * C::QP + col) = ov;
-    }
-    if (tid < BQ) {
-      const int tok = i * BQ + tid;
-      // rows past N get LSE = +inf, so their P is exactly zero
-      lse_s[tid] = tok < N ? a.lse[(int64_t)bh * N + tok] * LOG2E : INFINITY;
-      dlt_s[tid] = tok < N ? a.delta[(int64_t)bh * N + tok] : 0.f;
-    }
-    __syncthreads();
+    const bool more = t + 1 < cnt;
+    if (more) request_tile(idx[t + 1], (t + 1) & 1);
+    const int st = t & 1;
+    const uint16_t* Qb = smem + 2 * st * TILE;
+    const uint16_t* Ob = Qb + TILE;
+    const float* lb = lse_s + st * BQ + wq * 32;
+    const float* db = dlt_s + st * BQ + wq * 32;
+    // keep the XORed operand addresses out of loop-invariant hoisting: recomputing them costs one
+    // VALU op per read, keeping sixteen of them live costs registers this kernel does not have
+    asm volatile("" : "+v"(a_base), "+v"(t_base0), "+v"(t_base1));
 
+    f32x16 s, dp;
 #pragma unroll
-    for (int qc = 0; qc < 4; ++qc) {        // 32 queries at a time
-      f32x4 s[2], dp[2];
+    for (int v = 0; v < 16; ++v) { s[v] = 0.f; dp[v] = 0.f; }
 #pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        const int qb = 2 * qc + u;
-        s[u] = f32x4{0.f, 0.f, 0.f, 0.f};
-        dp[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int kk = 0; kk < D / 16; ++kk) {
+      const bf16x8 qa = *(const bf16x8*)(Qb + (a_base ^ (kk << 4)));
+      s = mfma32(qa, kf[kk], s);
+      const bf16x8 oa = *(const bf16x8*)(Ob + (a_base ^ (kk << 4)));
+      dp = mfma32(oa, vf[kk], dp);
+    }
+    // accumulator register v holds query 8*(v/4) + 4hf + v%4 of this wave's 32 queries
+    uint32_t pk[8], dsk[8];
 #pragma unroll
-        for (int kk = 0; kk < D / 32; ++kk) {
-          const bf16x8 qa = *(const bf16x8*)(Qs + a_off + qb * 16 * C::QP + 32 * kk);
-          s[u] = mfma16(qa, kf[kk], s[u]);
-          const bf16x8 oa = *(const bf16x8*)(Os + a_off + qb * 16 * C::QP + 32 * kk);
-          dp[u] = mfma16(oa, vf[kk], dp[u]);
-        }
-        const f32x4 l4 = *(const f32x4*)(lse_s + qb * 16 + 4 * G);
-        const f32x4 d4 = *(const f32x4*)(dlt_s + qb * 16 + 4 * G);
+    for (int g = 0; g < 4; ++g) {
+      const f32x4 l4 = *(const f32x4*)(lb + 8 * g + 4 * hf);
+      const f32x4 d4 = *(const f32x4*)(db + 8 * g + 4 * hf);
+      float p[4], ds[4];
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-          float p = fast_exp2(fmaf(s[u][v], a.scale_log2, -l4[v]));
-          if (!key_ok) p = 0.f;
-          s[u][v] = p;
-          dp[u][v] = p * (dp[u][v] - d4[v]);
-        }
+      for (int e = 0; e < 4; ++e) {
+        p[e] = fast_exp2(fmaf(s[4 * g + e], a.scale_log2, -l4[e]));
+        if (!key_ok) p[e] = 0.f;
+        ds[e] = p[e] * (dp[4 * g + e] - d4[e]);
       }
-      // this lane's 8 query slots: 32qc + 4G + {0..3} and 32qc + 16 + 4G + {0..3}
-      const bf16x8 pb = make_bf16x8(s[0][0], s[0][1], s[0][2], s[0][3], s[1][0], s[1][1], s[1][2], s[1][3]);
-      const bf16x8 dsb = make_bf16x8(dp[0][0], dp[0][1], dp[0][2], dp[0][3], dp[1][0], dp[1][1], dp[1][2], dp[1][3]);
-      const uint16_t* orow = Os + t_off + 32 * qc * C::QP;
-      const uint16_t* qrow = Qs + t_off + 32 * qc * C::QP;
+      pk[2 * g] = pack_bf16(p[0], p[1]);    pk[2 * g + 1] = pack_bf16(p[2], p[3]);
+      dsk[2 * g] = pack_bf16(ds[0], ds[1]); dsk[2 * g + 1] = pack_bf16(ds[2], ds[3]);
+    }
 #pragma unroll
-      for (int nb = 0; nb < D / 16; ++nb) {
-        const bf16x8 ot = join_tr(lds_read_tr4(orow + 16 * nb), lds_read_tr4(orow + 16 * C::QP + 16 * nb));
-        dv_acc[nb] = mfma16(ot, pb, dv_acc[nb]);
-        const bf16x8 qt = join_tr(lds_read_tr4(qrow + 16 * nb), lds_read_tr4(qrow + 16 * C::QP + 16 * nb));
-        dk_acc[nb] = mfma16(qt, dsb, dk_acc[nb]);
+    for (int c = 0; c < 2; ++c) {              // 16 queries per MFMA: slots 16c + 4hf + {0..3} and + 8
+      const u32x4 pu = {pk[4 * c], pk[4 * c + 1], pk[4 * c + 2], pk[4 * c + 3]};
+      const u32x4 du = {dsk[4 * c], dsk[4 * c + 1], dsk[4 * c + 2], dsk[4 * c + 3]};
+      const bf16x8 pb = __builtin_bit_cast(bf16x8, pu);
+      const bf16x8 dsb = __builtin_bit_cast(bf16x8, du);
+#pragma unroll
+      for (int mb = 0; mb < D / 32; ++mb) {
+        const int o0 = (t_base0 ^ (mb << 5)) + 16 * c * D, o1 = (t_base1 ^ (mb << 5)) + 16 * c * D;
+        const bf16x8 ot = join_tr(lds_read_tr4(Ob + o0), lds_read_tr4(Ob + o1));
+        dv_acc[mb] = mfma32(ot, pb, dv_acc[mb]);
+        const bf16x8 qt = join_tr(lds_read_tr4(Qb + o0), lds_read_tr4(Qb + o1));
+        dk_acc[mb] = mfma32(qt, dsb, dk_acc[mb]);
       }
     }
+    if (more) publish_stat((t + 1) & 1);
+    __syncthreads();      // also waits for the global -> LDS copies requested in this iteration
   }
 
-  // accumulators hold dK^T / dV^T: lane = key, registers = 4 consecutive channels 16nb + 4G ..
-  if (key_ok) {
-    const int64_t off = base + (int64_t)key * a.sn + 4 * G;
+  // sum the partial results of the four query groups of each key half.  Round 1: dK, round 2: dV.
+  // Wave (wq, wk) finishes output block mb = wq (channels 32wq..32wq+31) of its key half.
+  float* scratch = (float*)smem;
+  constexpr int REGION = (D / 32) * 16 * 64;          // floats per wave
 #pragma unroll
-    for (int nb = 0; nb < D / 16; ++nb) {
-      u32x2 pk = {pack_bf16(dk_acc[nb][0] * a.scale, dk_acc[nb][1] * a.scale),
-                  pack_bf16(dk_acc[nb][2] * a.scale, dk_acc[nb][3] * a.scale)};
-      *(u32x2*)(a.dk + off + 16 * nb) = pk;
-      u32x2 pv = {pack_bf16(dv_acc[nb][0], dv_acc[nb][1]), pack_bf16(dv_acc[nb][2], dv_acc[nb][3])};
-      *(u32x2*)(a.dv + off + 16 * nb) = pv;
+  for (int round = 0; round < 2; ++round) {
+    float* mine = scratch + w * REGION + lane;
+#pragma unroll
+    for (int mb = 0; mb < D / 32; ++mb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) mine[(mb * 16 + v) * 64] = round == 0 ? dk_acc[mb][v] : dv_acc[mb][v];
+    __syncthreads();
+    if (wq < D / 32 && key_ok) {
+      const int64_t out_off = base + (int64_t)key * a.sn + 4 * hf;
+      uint16_t* out = (round == 0 ? a.dk : a.dv) + out_off + 32 * wq;
+      const float sc = round == 0 ? a.scale : 1.f;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        float x[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int v = 4 * g + e;
+          float sum = 0.f;
+#pragma unroll
+          for (int pq = 0; pq < 4; ++pq) sum += scratch[(wk * 4 + pq) * REGION + (wq * 16 + v) * 64 + lane];
+          x[e] = sum * sc;
+        }
+        u32x2 pk2 = {pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3])};
+        *(u32x2*)(out + 8 * g) = pk2;
+      }
     }
+    __syncthreads();
   }
 }
 
@@ -392,7 +492,7 @@ hipError_t launch_bwd_dkdv(const void* q, const void* k, const void* v, const vo
   a.H = m.H; a.N = m.N; a.Tm = m.Tm; a.Tn = m.Tn; a.chunk = (m.Tn + 7) / 8;
   a.sb = m.sb; a.sh = m.sh; a.sn = m.sn;
   a.scale = scale; a.scale_log2 = scale * LOG2E;
-  const dim3 grid((unsigned)(m.B * m.H * 8 * a.chunk)), block(256);
+  const dim3 grid((unsigned)(m.B * m.H * 8 * a.chunk)), block(512);
   if (m.d == 128) hipLaunchKernelGGL(dkdv_kernel<128>, grid, block, 0, stream, a);
   else            hipLaunchKernelGGL(dkdv_kernel<64>, grid, block, 0, stream, a);
   return hipGetLastError();

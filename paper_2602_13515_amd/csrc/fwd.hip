@@ -34,6 +34,7 @@ struct FwdCfg {
   static constexpr int V_ELEMS = BKV * VP;
   static constexpr int CH = BKV * D / 8 / 256;   // 16-byte chunks per thread per tile
 };
+constexpr int PD = 4;   // how many MFMAs ahead an LDS operand is requested
 
 template <int D>
 __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdArgs a) {
@@ -52,9 +53,19 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdArgs a) {
   // address memory outside the tensors
   const int cnt = min(max(a.row_cnt[(int64_t)bh * a.Tm + i], 0), a.Tn);
   const int32_t* idx = a.row_idx + ((int64_t)bh * a.Tm + i) * a.Tn;
+  const int qrow = i * BQ + w * 32 + r32;
+
+  if (cnt == 0) {   // a row without any selected block (never produced by the masker): O = 0, LSE = -inf
+    if (qrow < N) {
+      uint16_t* op = a.o + base + (int64_t)qrow * a.sn + (D / 2) * hf;
+#pragma unroll
+      for (int c = 0; c < D / 16; ++c) *(u32x4*)(op + 8 * c) = u32x4{0, 0, 0, 0};
+      if (hf == 0) a.lse[(int64_t)bh * N + qrow] = -INFINITY;
+    }
+    return;
+  }
 
   // Q^T fragments (B operand): lane = query row, 8 consecutive channels per 16-wide k step.
-  const int qrow = i * BQ + w * 32 + r32;
   const int qrow_ld = qrow < N ? qrow : N - 1;
   bf16x8 qf[D / 16];
   {
@@ -63,32 +74,46 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdArgs a) {
     for (int kk = 0; kk < D / 16; ++kk) qf[kk] = *(const bf16x8*)(qp + 16 * kk);
   }
 
-  // global -> register staging of one K/V tile (rows past N read as zeros)
-  u32x4 kreg[C::CH], vreg[C::CH];
-  auto load_tile = [&](int j) {
-    j = min(max(j, 0), a.Tn - 1);
+  // global -> register staging of one K/V tile.  Thread t moves 16-byte chunk (row, col) with
+  // row = t / (D/8) + r * 256 / (D/8).  Rows past N (short last block) are clamped to the last
+  // token: their keys are masked out of the softmax below and their P is exactly zero, so the
+  // duplicated K/V rows never contribute.
+  constexpr int RSTEP = 256 / (D / 8);
+  const int ld_row = tid / (D / 8), ld_col = (tid % (D / 8)) * 8;
+  uint32_t goff[C::CH];          // byte offset of this thread's chunks inside a full tile
 #pragma unroll
-    for (int r = 0; r < C::CH; ++r) {
-      const int c = tid + 256 * r;
-      const int row = c / (D / 8), col = (c % (D / 8)) * 8;
-      const int tok = j * BKV + row;
-      if (tok < N) {
-        const int64_t off = base + (int64_t)tok * a.sn + col;
-        kreg[r] = *(const u32x4*)(a.k + off);
-        vreg[r] = *(const u32x4*)(a.v + off);
-      } else {
-        kreg[r] = u32x4{0, 0, 0, 0};
-        vreg[r] = u32x4{0, 0, 0, 0};
+  for (int r = 0; r < C::CH; ++r) goff[r] = (uint32_t)(((ld_row + RSTEP * r) * a.sn + ld_col) * 2);
+  const int lds_k = ld_row * C::KP + ld_col, lds_v = ld_row * C::VP + ld_col;
+  // Two staging sets: a tile is requested two iterations before it is needed, so that a request has
+  // two tiles' worth of compute to come back from L2 / HBM (one is not enough under load).
+  struct Stage { u32x4 k[C::CH], v[C::CH]; };
+  Stage stA, stB;
+  auto load_tile = [&](Stage& st, int j) {
+    j = min(max(j, 0), a.Tn - 1);
+    const int64_t tile = (base + (int64_t)j * BKV * a.sn) * 2;       // uniform
+    const char* kp = (const char*)a.k + tile;
+    const char* vp = (const char*)a.v + tile;
+    if ((j + 1) * BKV <= N) {
+#pragma unroll
+      for (int r = 0; r < C::CH; ++r) {
+        st.k[r] = *(const u32x4*)(kp + goff[r]);
+        st.v[r] = *(const u32x4*)(vp + goff[r]);
+      }
+    } else {
+      const int last = N - 1 - j * BKV;
+#pragma unroll
+      for (int r = 0; r < C::CH; ++r) {
+        const uint32_t o2 = (uint32_t)((min(ld_row + RSTEP * r, last) * a.sn + ld_col) * 2);
+        st.k[r] = *(const u32x4*)(kp + o2);
+        st.v[r] = *(const u32x4*)(vp + o2);
       }
     }
   };
-  auto store_tile = [&](int buf) {
+  auto store_tile = [&](const Stage& st, int buf) {
 #pragma unroll
     for (int r = 0; r < C::CH; ++r) {
-      const int c = tid + 256 * r;
-      const int row = c / (D / 8), col = (c % (D / 8)) * 8;
-      *(u32x4*)(Ks + buf * C::K_ELEMS + row * C::KP + col) = kreg[r];
-      *(u32x4*)(Vs + buf * C::V_ELEMS + row * C::VP + col) = vreg[r];
+      *(u32x4*)(Ks + buf * C::K_ELEMS + lds_k + RSTEP * r * C::KP) = st.k[r];
+      *(u32x4*)(Vs + buf * C::V_ELEMS + lds_v + RSTEP * r * C::VP) = st.v[r];
     }
   };
 
@@ -105,31 +130,57 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdArgs a) {
   const int s16 = lane & 15, blk16 = lane >> 4;
   const int v_off = (4 * hf + (s16 >> 2)) * C::VP + 16 * (blk16 & 1) + 4 * (s16 & 3);  // V transposing read
 
-  if (cnt > 0) {
-    load_tile(idx[0]);
-    store_tile(0);
-  }
+  // Pipeline: tile T is requested at the start of iteration T-3 into the staging set of its parity,
+  // written to LDS buffer T&1 at the start of iteration T-1 (that buffer held tile T-2, fully consumed
+  // before the barrier that ended iteration T-2), and consumed in iteration T.  Two tiles are in flight
+  // at any time and one barrier per tile is enough.
+  load_tile(stA, idx[0]);
+  store_tile(stA, 0);
+  if (cnt > 1) load_tile(stB, idx[1]);
+  if (cnt > 2) load_tile(stA, idx[2]);
   __syncthreads();
 
-  for (int t = 0; t < cnt; ++t) {
+  auto iteration = [&](int t, Stage& next, Stage& /*unused*/) {
     const int j = min(max(idx[t], 0), a.Tn - 1);
-    const bool more = t + 1 < cnt;
-    if (more) load_tile(idx[t + 1]);
+    if (t + 1 < cnt) store_tile(next, (t + 1) & 1);
+    if (t + 3 < cnt) load_tile(next, idx[t + 3]);
     const uint16_t* Kb = Ks + (t & 1) * C::K_ELEMS;
     const uint16_t* Vb = Vs + (t & 1) * C::V_ELEMS;
 
-    // S^T = K_j Q_i^T : two 32-key blocks
+    // S^T = K_j Q_i^T : two 32-key blocks.  LDS operand reads run PD MFMAs ahead of their use.
     f32x16 s[2];
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
+    for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int v = 0; v < 16; ++v) s[kb][v] = 0.f;
+    {
+      constexpr int NQK = 2 * (D / 16);
+      bf16x8 kfr[PD];
 #pragma unroll
-      for (int kk = 0; kk < D / 16; ++kk) {
-        const bf16x8 ka = *(const bf16x8*)(Kb + k_off + kb * 32 * C::KP + 16 * kk);
-        s[kb] = mfma32(ka, qf[kk], s[kb]);
+      for (int x = 0; x < PD; ++x)
+        kfr[x] = *(const bf16x8*)(Kb + k_off + (x / (D / 16)) * 32 * C::KP + 16 * (x % (D / 16)));
+#pragma unroll
+      for (int x = 0; x < NQK; ++x) {
+        const int kb = x / (D / 16), kk = x % (D / 16);
+        s[kb] = mfma32(kfr[x % PD], qf[kk], s[kb]);
+        if (x + PD < NQK) {
+          const int y = x + PD;
+          kfr[x % PD] = *(const bf16x8*)(Kb + k_off + (y / (D / 16)) * 32 * C::KP + 16 * (y % (D / 16)));
+        }
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
+    // first V^T operands of the second product are requested now, so that they arrive during the softmax
+    constexpr int NPV = 4 * (D / 32);
+    bf16x8 vfr[PD];
+    auto v_frag = [&](int y) {
+      const int kb = y / (2 * (D / 32)), cc = (y / (D / 32)) % 2, mb = y % (D / 32);
+      const uint16_t* vrow = Vb + v_off + (32 * kb + 16 * cc) * C::VP + 32 * mb;
+      return join_tr(lds_read_tr4(vrow), lds_read_tr4(vrow + 8 * C::VP));
+    };
+#pragma unroll
+    for (int x = 0; x < PD; ++x) vfr[x] = v_frag(x);
+    __builtin_amdgcn_sched_barrier(0);
     // keys past N (short last block) do not take part in the softmax
     if ((j + 1) * BKV > N) {
 #pragma unroll
@@ -148,56 +199,61 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdArgs a) {
     for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[1][v]);
     mx = fmaxf(mx, other_half(mx));
     const float m_new = fmaxf(m_run, mx * a.scale_log2);
-    const float alpha = fast_exp2(m_run - m_new);
-    // P^T = exp(S^T - m) (step 12), partial row sum (step 13)
-    float rs = 0.f;
+    // rescale the accumulators (steps 13-14) only when some row's maximum moved: after the first
+    // few tiles it rarely does, and the branch is uniform over the wave
+    if (__builtin_amdgcn_ballot_w64(m_new != m_run) != 0) {
+      const float alpha = fast_exp2(m_run - m_new);
+      l_run *= alpha;
+#pragma unroll
+      for (int mb = 0; mb < D / 32; ++mb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) oacc[mb][v] *= alpha;
+      m_run = m_new;
+    }
+    // P^T = exp(S^T - m) (step 12), rounded to bf16 for the second product; the row sum (step 13)
+    // is taken over the rounded values, so numerator and denominator use the same weights
+    uint32_t pk[2][8];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const float p = fast_exp2(fmaf(s[kb][v], a.scale_log2, -m_new));
-        s[kb][v] = p;
-        rs += p;
+      for (int u = 0; u < 8; ++u) {
+        const float p0 = fast_exp2(fmaf(s[kb][2 * u], a.scale_log2, -m_run));
+        const float p1 = fast_exp2(fmaf(s[kb][2 * u + 1], a.scale_log2, -m_run));
+        pk[kb][u] = pack_bf16(p0, p1);
+        l_run = dot2_ones(pk[kb][u], l_run);
       }
-    l_run = fmaf(l_run, alpha, rs);
-    m_run = m_new;
-    // O^T = diag(alpha) O^T + V^T P^T (step 14)
+    // O^T += V^T P^T (step 14).  MFMA x uses key slots 32kb + 16cc + 4hf + {0..3} and + 8 (the order the
+    // accumulator of S^T holds them in) of output block mb.
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int mb = 0; mb < D / 32; ++mb)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) oacc[mb][v] *= alpha;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int cc = 0; cc < 2; ++cc) {
-        // key slots of this lane: 32kb + 16cc + 4hf + {0..3} and +8: the order the accumulator holds them in
-        const bf16x8 pb = make_bf16x8(s[kb][8 * cc + 0], s[kb][8 * cc + 1], s[kb][8 * cc + 2], s[kb][8 * cc + 3],
-                                      s[kb][8 * cc + 4], s[kb][8 * cc + 5], s[kb][8 * cc + 6], s[kb][8 * cc + 7]);
-        const uint16_t* vrow = Vb + v_off + (32 * kb + 16 * cc) * C::VP;
-#pragma unroll
-        for (int mb = 0; mb < D / 32; ++mb) {
-          const bf16x8 va = join_tr(lds_read_tr4(vrow + 32 * mb), lds_read_tr4(vrow + 8 * C::VP + 32 * mb));
-          oacc[mb] = mfma32(va, pb, oacc[mb]);
-        }
-      }
-    if (more) store_tile((t + 1) & 1);
+    for (int x = 0; x < NPV; ++x) {
+      const int kb = x / (2 * (D / 32)), cc = (x / (D / 32)) % 2, mb = x % (D / 32);
+      const u32x4 pu = {pk[kb][4 * cc], pk[kb][4 * cc + 1], pk[kb][4 * cc + 2], pk[kb][4 * cc + 3]};
+      oacc[mb] = mfma32(vfr[x % PD], __builtin_bit_cast(bf16x8, pu), oacc[mb]);
+      if (x + PD < NPV) vfr[x % PD] = v_frag(x + PD);
+      __builtin_amdgcn_sched_barrier(0);
+    }
     __syncthreads();
+  };
+  for (int t = 0; t < cnt; t += 2) {
+    iteration(t, stB, stA);                       // tile t+1 (odd) lives in set B
+    if (t + 1 < cnt) iteration(t + 1, stA, stB);  // tile t+2 (even) lives in set A
   }
 
   // O_i = diag(l)^-1 O (step 18) and the log-sum-exp the backward pass needs
   const float l_tot = l_run + other_half(l_run);
-  const float inv = cnt > 0 ? 1.f / l_tot : 0.f;
+  const float inv = 1.f / l_tot;
   if (qrow < N) {
     uint16_t* op = a.o + base + (int64_t)qrow * a.sn + 4 * hf;
 #pragma unroll
     for (int mb = 0; mb < D / 32; ++mb)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        u32x2 pk = {pack_bf16(oacc[mb][4 * g + 0] * inv, oacc[mb][4 * g + 1] * inv),
-                    pack_bf16(oacc[mb][4 * g + 2] * inv, oacc[mb][4 * g + 3] * inv)};
-        *(u32x2*)(op + 32 * mb + 8 * g) = pk;
+        u32x2 pk2 = {pack_bf16(oacc[mb][4 * g + 0] * inv, oacc[mb][4 * g + 1] * inv),
+                     pack_bf16(oacc[mb][4 * g + 2] * inv, oacc[mb][4 * g + 3] * inv)};
+        *(u32x2*)(op + 32 * mb + 8 * g) = pk2;
       }
-    if (hf == 0) a.lse[(int64_t)bh * N + qrow] = cnt > 0 ? m_run * LN2 + __logf(l_tot) : -INFINITY;
+    if (hf == 0) a.lse[(int64_t)bh * N + qrow] = m_run * LN2 + __logf(l_tot);
   }
 }
 

@@ -71,7 +71,25 @@ __device__ __forceinline__ float other_half(float x) {
   return __shfl_xor(x, 32, 64);
 }
 
+// acc + lo(p) + hi(p) for a packed bf16 pair p, accumulated in fp32 (v_dot2c_f32_bf16 with a pair of ones)
+__device__ __forceinline__ float dot2_ones(uint32_t p, float acc) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, p), __builtin_bit_cast(bf16x2, 0x3f803f80u), acc,
+                                         false);
+}
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// XOR-swizzled LDS tile: rows of D bf16, unpadded; the 16-byte chunk c of row r lives at chunk position
+// c ^ swz<D>(r).  The function is chosen so that BOTH access patterns the kernels use are free of bank
+// conflicts (64 banks x 4 bytes): 16 lanes reading the same chunk of 16 consecutive rows (MFMA operand read
+// along rows), and 32 lanes reading 64 contiguous bytes of each of 4 consecutive rows (transposing read).
+template <int D> __device__ __forceinline__ int swz(int r);
+template <> __device__ __forceinline__ int swz<128>(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
+template <> __device__ __forceinline__ int swz<64>(int r) { return (((r >> 1) & 1) << 2) | ((r >> 2) & 3); }
+// element index of logical (row, col) in a swizzled tile
+template <int D> __device__ __forceinline__ int swz_idx(int row, int col) {
+  return row * D + ((((col >> 3) ^ swz<D>(row))) << 3) + (col & 7);
+}
 
 // Workgroup id -> (head, block) mapping that keeps one head's blocks resident
 // on all eight XCDs at once: consecutive workgroup ids go round-robin to the
