@@ -71,6 +71,14 @@ typedef struct spa2_pattern {
   int32_t* row_idx;   /* [B,H,T_m,T_n]  first row_cnt entries valid, ascending j      */
   int32_t* col_cnt;   /* [B,H,T_n]      number of query blocks that selected key block j */
   int32_t* col_idx;   /* [B,H,T_n,T_m]  first col_cnt entries valid, ascending i      */
+  /* Optional launch orders (NULL = natural order).  They do not change any result: they only say in which
+   * order the attention kernels walk the query blocks (row_order, a permutation of 0..T_m-1 per head) and the
+   * key blocks (col_order, a permutation of 0..T_n-1 per head).  col_order is written by spa2_mask /
+   * spa2_mask_columns when non-NULL (longest column first, dealt evenly to the XCDs: it balances the
+   * dK/dV kernel); row_order is an input only (a caller that knows which query blocks select similar
+   * key blocks can place them next to each other), the library never writes it. */
+  int32_t* row_order; /* [B,H,T_m] or NULL */
+  int32_t* col_order; /* [B,H,T_n] or NULL */
 } spa2_pattern;
 
 int spa2_version(void);

@@ -36,7 +36,8 @@ class _Shape(ctypes.Structure):
 
 class _Pattern(ctypes.Structure):
     _fields_ = [("mask", ctypes.c_void_p), ("row_cnt", ctypes.c_void_p), ("row_idx", ctypes.c_void_p),
-                ("col_cnt", ctypes.c_void_p), ("col_idx", ctypes.c_void_p)]
+                ("col_cnt", ctypes.c_void_p), ("col_idx", ctypes.c_void_p),
+                ("row_order", ctypes.c_void_p), ("col_order", ctypes.c_void_p)]
 
 
 _lib = None
@@ -102,14 +103,18 @@ class Pattern:
     row_idx: torch.Tensor    # int32 [B,H,Tm,Tn]
     col_cnt: Optional[torch.Tensor]  # int32 [B,H,Tn]
     col_idx: Optional[torch.Tensor]  # int32 [B,H,Tn,Tm]
+    row_order: Optional[torch.Tensor] = None  # int32 [B,H,Tm] launch order of query blocks (optional)
+    col_order: Optional[torch.Tensor] = None  # int32 [B,H,Tn] launch order of key blocks (optional)
 
     def _c(self) -> _Pattern:
         return _Pattern(self.mask.data_ptr(), self.row_cnt.data_ptr(), self.row_idx.data_ptr(),
                         self.col_cnt.data_ptr() if self.col_cnt is not None else None,
-                        self.col_idx.data_ptr() if self.col_idx is not None else None)
+                        self.col_idx.data_ptr() if self.col_idx is not None else None,
+                        self.row_order.data_ptr() if self.row_order is not None else None,
+                        self.col_order.data_ptr() if self.col_order is not None else None)
 
 
-def alloc_pattern(B: int, H: int, N: int, device, columns: bool = True) -> Pattern:
+def alloc_pattern(B: int, H: int, N: int, device, columns: bool = True, col_order: bool = True) -> Pattern:
     Tm, Tn = -(-N // BQ), -(-N // BKV)
     i32 = torch.int32
     return Pattern(
@@ -118,6 +123,7 @@ def alloc_pattern(B: int, H: int, N: int, device, columns: bool = True) -> Patte
         row_idx=torch.empty((B, H, Tm, Tn), dtype=i32, device=device),
         col_cnt=torch.empty((B, H, Tn), dtype=i32, device=device) if columns else None,
         col_idx=torch.empty((B, H, Tn, Tm), dtype=i32, device=device) if columns else None,
+        col_order=torch.empty((B, H, Tn), dtype=i32, device=device) if (columns and col_order) else None,
     )
 
 

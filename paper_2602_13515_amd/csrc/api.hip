@@ -112,7 +112,7 @@ int spa2_mask_columns(const spa2_shape* shape, spa2_pattern* out, void* stream) 
   if (rc != SPA2_OK) return rc;
   if (!out || !out->mask || !out->col_cnt || !out->col_idx) return SPA2_ERR_NULL;
   const Dims m = make_dims(*shape);
-  return launch_columns(out->mask, m, out->col_cnt, out->col_idx, (hipStream_t)stream) == hipSuccess
+  return launch_columns(out->mask, m, out->col_cnt, out->col_idx, out->col_order, (hipStream_t)stream) == hipSuccess
              ? SPA2_OK : SPA2_ERR_LAUNCH;
 }
 
@@ -148,7 +148,7 @@ int spa2_pattern_full(const spa2_shape* shape, spa2_pattern* out, void* stream) 
   if ((out->col_cnt == nullptr) != (out->col_idx == nullptr)) return SPA2_ERR_NULL;
   const Dims m = make_dims(*shape);
   if (launch_pattern_full(m, out->mask, out->row_cnt, out->row_idx, out->col_cnt, out->col_idx,
-                          (hipStream_t)stream) != hipSuccess)
+                          out->col_cnt ? out->col_order : nullptr, (hipStream_t)stream) != hipSuccess)
     return SPA2_ERR_LAUNCH;
   return SPA2_OK;
 }
@@ -161,7 +161,8 @@ int spa2_fwd(const void* q, const void* k, const void* v, const spa2_shape* shap
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return SPA2_ERR_ALIGN;
   if (!(scale > 0.f) || !isfinite(scale)) return SPA2_ERR_RANGE;
   const Dims m = make_dims(*shape);
-  if (launch_fwd(q, k, v, m, pattern->row_cnt, pattern->row_idx, scale, o, lse, (hipStream_t)stream) != hipSuccess)
+  if (launch_fwd(q, k, v, m, pattern->row_cnt, pattern->row_idx, pattern->row_order, scale, o, lse,
+                 (hipStream_t)stream) != hipSuccess)
     return SPA2_ERR_LAUNCH;
   return SPA2_OK;
 }
@@ -192,8 +193,8 @@ int spa2_bwd_dkdv(const void* q, const void* k, const void* v, const void* d_o, 
   const Dims m = make_dims(*shape);
   if (!workspace || workspace_bytes < bwd_ws_bytes(m)) return SPA2_ERR_WORKSPACE;
   if (!aligned16(workspace)) return SPA2_ERR_ALIGN;
-  return launch_bwd_dkdv(q, k, v, d_o, lse, (const float*)workspace, m, pattern->col_cnt, pattern->col_idx, scale,
-                         dk, dv, (hipStream_t)stream) == hipSuccess ? SPA2_OK : SPA2_ERR_LAUNCH;
+  return launch_bwd_dkdv(q, k, v, d_o, lse, (const float*)workspace, m, pattern->col_cnt, pattern->col_idx,
+                         pattern->col_order, scale, dk, dv, (hipStream_t)stream) == hipSuccess ? SPA2_OK : SPA2_ERR_LAUNCH;
 }
 
 int spa2_bwd_dq(const void* q, const void* k, const void* v, const void* d_o, const float* lse,
@@ -208,8 +209,8 @@ int spa2_bwd_dq(const void* q, const void* k, const void* v, const void* d_o, co
   const Dims m = make_dims(*shape);
   if (!workspace || workspace_bytes < bwd_ws_bytes(m)) return SPA2_ERR_WORKSPACE;
   if (!aligned16(workspace)) return SPA2_ERR_ALIGN;
-  return launch_bwd_dq(q, k, v, d_o, lse, (const float*)workspace, m, pattern->row_cnt, pattern->row_idx, scale,
-                       dq, (hipStream_t)stream) == hipSuccess ? SPA2_OK : SPA2_ERR_LAUNCH;
+  return launch_bwd_dq(q, k, v, d_o, lse, (const float*)workspace, m, pattern->row_cnt, pattern->row_idx,
+                       pattern->row_order, scale, dq, (hipStream_t)stream) == hipSuccess ? SPA2_OK : SPA2_ERR_LAUNCH;
 }
 
 int spa2_bwd(const void* q, const void* k, const void* v, const void* o, const void* d_o, const float* lse,

@@ -62,7 +62,7 @@ hipError_t launch_bwd_delta(const void* o, const void* d_o, const Dims& m, float
 struct DqArgs {
   const uint16_t* q; const uint16_t* k; const uint16_t* v; const uint16_t* d_o;
   const float* lse; const float* delta; uint16_t* dq;
-  const int32_t* row_cnt; const int32_t* row_idx;
+  const int32_t* row_cnt; const int32_t* row_idx; const int32_t* row_order;
   int H, N, Tm, Tn, chunk;
   int64_t sb, sh, sn;
   float scale, scale_log2;
@@ -88,7 +88,8 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(DqArgs a) {
 
   const HeadBlock hb = xcd_map(blockIdx.x, a.Tm, a.chunk);
   if (!hb.valid) return;
-  const int bh = hb.bh, i = hb.blk;
+  const int bh = hb.bh;
+  const int i = a.row_order ? min(max(a.row_order[(int64_t)bh * a.Tm + hb.blk], 0), a.Tm - 1) : hb.blk;
   const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int r32 = lane & 31, hf = lane >> 5;
@@ -254,11 +255,11 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(DqArgs a) {
 
 hipError_t launch_bwd_dq(const void* q, const void* k, const void* v, const void* d_o, const float* lse,
                          const float* delta, const Dims& m, const int32_t* row_cnt, const int32_t* row_idx,
-                         float scale, void* dq, hipStream_t stream) {
+                         const int32_t* row_order, float scale, void* dq, hipStream_t stream) {
   DqArgs a;
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v; a.d_o = (const uint16_t*)d_o;
   a.lse = lse; a.delta = delta; a.dq = (uint16_t*)dq;
-  a.row_cnt = row_cnt; a.row_idx = row_idx;
+  a.row_cnt = row_cnt; a.row_idx = row_idx; a.row_order = row_order;
   a.H = m.H; a.N = m.N; a.Tm = m.Tm; a.Tn = m.Tn; a.chunk = (m.Tm + 7) / 8;
   a.sb = m.sb; a.sh = m.sh; a.sn = m.sn;
   a.scale = scale; a.scale_log2 = scale * LOG2E;
@@ -272,7 +273,7 @@ hipError_t launch_bwd_dq(const void* q, const void* k, const void* v, const void
 struct DkvArgs {
   const uint16_t* q; const uint16_t* k; const uint16_t* v; const uint16_t* d_o;
   const float* lse; const float* delta; uint16_t* dk; uint16_t* dv;
-  const int32_t* col_cnt; const int32_t* col_idx;
+  const int32_t* col_cnt; const int32_t* col_idx; const int32_t* col_order;
   int H, N, Tm, Tn, chunk;
   int64_t sb, sh, sn;
   float scale, scale_log2;
@@ -304,7 +305,8 @@ __global__ __launch_bounds__(512, 2) void dkdv_kernel(DkvArgs a) {
 
   const HeadBlock hbk = xcd_map(blockIdx.x, a.Tn, a.chunk);
   if (!hbk.valid) return;
-  const int bh = hbk.bh, j = hbk.blk;
+  const int bh = hbk.bh;
+  const int j = a.col_order ? min(max(a.col_order[(int64_t)bh * a.Tn + hbk.blk], 0), a.Tn - 1) : hbk.blk;
   const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int wq = w & 3, wk = w >> 2;
@@ -368,12 +370,14 @@ __global__ __launch_bounds__(512, 2) void dkdv_kernel(DkvArgs a) {
     }
     if (tid < 2 * BQ) {
       const int srow = i * BQ + (tid & (BQ - 1));
-      if (srow < N) stat = tid < BQ ? a.lse[(int64_t)bh * N + srow] * LOG2E : a.delta[(int64_t)bh * N + srow];
+      // (the conversion of LSE to log2 units is left to publish_stat: using the value here would make
+      // the wave wait for every copy requested above)
+      if (srow < N) stat = tid < BQ ? a.lse[(int64_t)bh * N + srow] : a.delta[(int64_t)bh * N + srow];
       else          stat = tid < BQ ? INFINITY : 0.f;
     }
   };
   auto publish_stat = [&](int stage) {
-    if (tid < BQ) lse_s[stage * BQ + tid] = stat;
+    if (tid < BQ) lse_s[stage * BQ + tid] = stat * LOG2E;
     else if (tid < 2 * BQ) dlt_s[stage * BQ + tid - BQ] = stat;
   };
 
@@ -402,17 +406,27 @@ __global__ __launch_bounds__(512, 2) void dkdv_kernel(DkvArgs a) {
     // VALU op per read, keeping sixteen of them live costs registers this kernel does not have
     asm volatile("" : "+v"(a_base), "+v"(t_base0), "+v"(t_base1));
 
+    // --- S and dP: LDS operands are requested two MFMA pairs ahead of their use
     f32x16 s, dp;
 #pragma unroll
     for (int v = 0; v < 16; ++v) { s[v] = 0.f; dp[v] = 0.f; }
+    {
+      bf16x8 fq[2], fo[2];
 #pragma unroll
-    for (int kk = 0; kk < D / 16; ++kk) {
-      const bf16x8 qa = *(const bf16x8*)(Qb + (a_base ^ (kk << 4)));
-      s = mfma32(qa, kf[kk], s);
-      const bf16x8 oa = *(const bf16x8*)(Ob + (a_base ^ (kk << 4)));
-      dp = mfma32(oa, vf[kk], dp);
+      for (int x = 0; x < 2; ++x) {
+        fq[x] = *(const bf16x8*)(Qb + (a_base ^ (x << 4)));
+        fo[x] = *(const bf16x8*)(Ob + (a_base ^ (x << 4)));
+      }
+#pragma unroll
+      for (int kk = 0; kk < D / 16; ++kk) {
+        s = mfma32(fq[kk & 1], kf[kk], s);
+        if (kk + 2 < D / 16) fq[kk & 1] = *(const bf16x8*)(Qb + (a_base ^ ((kk + 2) << 4)));
+        dp = mfma32(fo[kk & 1], vf[kk], dp);
+        if (kk + 2 < D / 16) fo[kk & 1] = *(const bf16x8*)(Ob + (a_base ^ ((kk + 2) << 4)));
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
-    // accumulator register v holds query 8*(v/4) + 4hf + v%4 of this wave's 32 queries
+    // --- P and dS.  Accumulator register v holds query 8*(v/4) + 4hf + v%4 of this wave's 32 queries.
     uint32_t pk[8], dsk[8];
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
@@ -428,19 +442,29 @@ __global__ __launch_bounds__(512, 2) void dkdv_kernel(DkvArgs a) {
       pk[2 * g] = pack_bf16(p[0], p[1]);    pk[2 * g + 1] = pack_bf16(p[2], p[3]);
       dsk[2 * g] = pack_bf16(ds[0], ds[1]); dsk[2 * g + 1] = pack_bf16(ds[2], ds[3]);
     }
+    __builtin_amdgcn_sched_barrier(0);
+    // --- dV^T and dK^T.  MFMA pair x = (c, mb): 16 queries per MFMA (slots 16c + 4hf + {0..3} and + 8),
+    // output block mb; transposed operands requested PDT pairs ahead.
+    {
+      constexpr int NX = 2 * (D / 32), PDT = 2;
+      auto tr_frag = [&](const uint16_t* tile, int x) {
+        const int c = x / (D / 32), mb = x % (D / 32);
+        return join_tr(lds_read_tr4(tile + (t_base0 ^ (mb << 5)) + 16 * c * D),
+                       lds_read_tr4(tile + (t_base1 ^ (mb << 5)) + 16 * c * D));
+      };
+      bf16x8 fo[PDT], fq[PDT];
 #pragma unroll
-    for (int c = 0; c < 2; ++c) {              // 16 queries per MFMA: slots 16c + 4hf + {0..3} and + 8
-      const u32x4 pu = {pk[4 * c], pk[4 * c + 1], pk[4 * c + 2], pk[4 * c + 3]};
-      const u32x4 du = {dsk[4 * c], dsk[4 * c + 1], dsk[4 * c + 2], dsk[4 * c + 3]};
-      const bf16x8 pb = __builtin_bit_cast(bf16x8, pu);
-      const bf16x8 dsb = __builtin_bit_cast(bf16x8, du);
+      for (int x = 0; x < PDT; ++x) { fo[x] = tr_frag(Ob, x); fq[x] = tr_frag(Qb, x); }
 #pragma unroll
-      for (int mb = 0; mb < D / 32; ++mb) {
-        const int o0 = (t_base0 ^ (mb << 5)) + 16 * c * D, o1 = (t_base1 ^ (mb << 5)) + 16 * c * D;
-        const bf16x8 ot = join_tr(lds_read_tr4(Ob + o0), lds_read_tr4(Ob + o1));
-        dv_acc[mb] = mfma32(ot, pb, dv_acc[mb]);
-        const bf16x8 qt = join_tr(lds_read_tr4(Qb + o0), lds_read_tr4(Qb + o1));
-        dk_acc[mb] = mfma32(qt, dsb, dk_acc[mb]);
+      for (int x = 0; x < NX; ++x) {
+        const int c = x / (D / 32), mb = x % (D / 32);
+        const u32x4 pu = {pk[4 * c], pk[4 * c + 1], pk[4 * c + 2], pk[4 * c + 3]};
+        const u32x4 du = {dsk[4 * c], dsk[4 * c + 1], dsk[4 * c + 2], dsk[4 * c + 3]};
+        dv_acc[mb] = mfma32(fo[x % PDT], __builtin_bit_cast(bf16x8, pu), dv_acc[mb]);
+        if (x + PDT < NX) fo[x % PDT] = tr_frag(Ob, x + PDT);
+        dk_acc[mb] = mfma32(fq[x % PDT], __builtin_bit_cast(bf16x8, du), dk_acc[mb]);
+        if (x + PDT < NX) fq[x % PDT] = tr_frag(Qb, x + PDT);
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
     if (more) publish_stat((t + 1) & 1);
@@ -484,11 +508,11 @@ __global__ __launch_bounds__(512, 2) void dkdv_kernel(DkvArgs a) {
 
 hipError_t launch_bwd_dkdv(const void* q, const void* k, const void* v, const void* d_o, const float* lse,
                            const float* delta, const Dims& m, const int32_t* col_cnt, const int32_t* col_idx,
-                           float scale, void* dk, void* dv, hipStream_t stream) {
+                           const int32_t* col_order, float scale, void* dk, void* dv, hipStream_t stream) {
   DkvArgs a;
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v; a.d_o = (const uint16_t*)d_o;
   a.lse = lse; a.delta = delta; a.dk = (uint16_t*)dk; a.dv = (uint16_t*)dv;
-  a.col_cnt = col_cnt; a.col_idx = col_idx;
+  a.col_cnt = col_cnt; a.col_idx = col_idx; a.col_order = col_order;
   a.H = m.H; a.N = m.N; a.Tm = m.Tm; a.Tn = m.Tn; a.chunk = (m.Tn + 7) / 8;
   a.sb = m.sb; a.sh = m.sh; a.sn = m.sn;
   a.scale = scale; a.scale_log2 = scale * LOG2E;

@@ -20,7 +20,7 @@ namespace spa2 {
 struct FwdArgs {
   const uint16_t* q; const uint16_t* k; const uint16_t* v;
   uint16_t* o; float* lse;
-  const int32_t* row_cnt; const int32_t* row_idx;
+  const int32_t* row_cnt; const int32_t* row_idx; const int32_t* row_order;
   int H, N, Tm, Tn, chunk;
   int64_t sb, sh, sn;
   float scale_log2;     // scale * log2(e): softmax is evaluated with exp2
@@ -44,7 +44,9 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdArgs a) {
 
   const HeadBlock hb = xcd_map(blockIdx.x, a.Tm, a.chunk);
   if (!hb.valid) return;
-  const int bh = hb.bh, i = hb.blk;
+  const int bh = hb.bh;
+  // optional launch order: position hb.blk of this head's schedule -> query block (clamped: caller data)
+  const int i = a.row_order ? min(max(a.row_order[(int64_t)bh * a.Tm + hb.blk], 0), a.Tm - 1) : hb.blk;
   const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int r32 = lane & 31, hf = lane >> 5;
@@ -258,11 +260,12 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdArgs a) {
 }
 
 hipError_t launch_fwd(const void* q, const void* k, const void* v, const Dims& m, const int32_t* row_cnt,
-                      const int32_t* row_idx, float scale, void* o, float* lse, hipStream_t stream) {
+                      const int32_t* row_idx, const int32_t* row_order, float scale, void* o, float* lse,
+                      hipStream_t stream) {
   FwdArgs a;
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v;
   a.o = (uint16_t*)o; a.lse = lse;
-  a.row_cnt = row_cnt; a.row_idx = row_idx;
+  a.row_cnt = row_cnt; a.row_idx = row_idx; a.row_order = row_order;
   a.H = m.H; a.N = m.N; a.Tm = m.Tm; a.Tn = m.Tn;
   a.chunk = (m.Tm + 7) / 8;
   a.sb = m.sb; a.sh = m.sh; a.sn = m.sn;

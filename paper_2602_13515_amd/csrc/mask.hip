@@ -113,19 +113,44 @@ __device__ __forceinline__ T segment_scan(T x, int tid, int seg_threads, T* sm4,
   return pre + excl;
 }
 
-// NP: padded row length (power of two >= T_n, >= 256).  R rows of one head per workgroup.
+// Pbar in [0, 2) as a 62-bit fixed-point integer (truncated below 2^-62): sums of these are exact and do
+// not depend on the order of addition, which makes the Top-p comparison deterministic under LDS atomics.
+__device__ __forceinline__ uint64_t fixed62(uint32_t fbits) {
+  const int e = (int)(fbits >> 23);                 // the sign bit is clear
+  if (e == 0) return 0;                             // zero or denormal
+  const uint64_t m = (uint64_t)((fbits & 0x7fffffu) | 0x800000u);
+  const int sh = e - 88;                            // value = m * 2^(e-150); times 2^62
+  return sh >= 0 ? (m << sh) : (sh > -24 ? (m >> (-sh)) : 0);
+}
+
+// NP: padded row length (power of two >= T_n, >= 256).  R = 4 rows of one head per workgroup.
+//
+// Selection without sorting.  Entries are ordered by the 64-bit key (bits(Pbar) << 32) | ~j (larger Pbar
+// first, equal Pbar: lower block index first).  With cnt_gt(e) / mass_gt(e) the number / total Pbar of
+// the entries whose key is greater than e's, the rule "first max(1, k_cnt, n_p) entries of the order,
+// n_p = shortest prefix with sum >= p" is the same as
+//        e selected  <=>  cnt_gt(e) < max(1, k_cnt)  or  mass_gt(e) < p,
+// a predicate that is monotone in the key, so the selected set is {key >= T}.  T is found by a radix
+// descent over the key, 8 bits per pass (6 passes: four over the bits of Pbar, two over the index bits
+// that break ties): per pass a 256-bin histogram of count and mass of the entries that match the prefix
+// found so far, then one wave per row walks the bins from the top and picks the lowest bin whose top
+// entry is still selected.
 template <int NP, int R>
 __global__ __launch_bounds__(256) void select_kernel(SelArgs a) {
+  static_assert(R == 4, "one wave scans the histogram of one row");
   constexpr int JJ = NP / 256;            // score columns per thread per row
-  constexpr int E = R * NP / 256;         // consecutive sorted / index-ordered elements per thread
-  constexpr int SEG_T = 256 / R;          // threads per row in the scans
-  __shared__ uint64_t keys[R * NP];
-  __shared__ double qd[R][128];
+  constexpr int G = JJ < 8 ? JJ : 8;      // columns per thread processed together in the score loop
+  constexpr int E = R * NP / 256;         // consecutive block indices per thread in the compaction pass
+  constexpr int SEG_T = 256 / R;          // threads per row in the compaction pass
+  __shared__ uint32_t h_cnt[R][256];
+  __shared__ uint64_t h_mass[R][256];
+  __shared__ __align__(16) double qd[128][R];
   __shared__ uint8_t flag[R * NP];
   __shared__ float redf[R][4];
-  __shared__ double sm4d[4];
   __shared__ int sm4i[4];
-  __shared__ int n_sel[R];
+  __shared__ uint64_t st_key[R];          // key prefix found so far (lower bits zero)
+  __shared__ uint32_t st_cnt[R];          // number of entries above the prefix range
+  __shared__ uint64_t st_mass[R];         // their mass
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int bh = blockIdx.x / a.groups;
@@ -135,29 +160,42 @@ __global__ __launch_bounds__(256) void select_kernel(SelArgs a) {
 
   for (int x = tid; x < R * d; x += 256) {
     const int r = x / d, c = x % d;
-    qd[r][c] = r < nrows ? (double)a.qbar[((int64_t)bh * a.Tm + i0 + r) * d + c] : 0.0;
+    qd[c][r] = r < nrows ? (double)a.qbar[((int64_t)bh * a.Tm + i0 + r) * d + c] : 0.0;
   }
   for (int x = tid; x < R * NP; x += 256) flag[x] = 0;
+  for (int x = tid; x < R * 256; x += 256) { h_cnt[x >> 8][x & 255] = 0; h_mass[x >> 8][x & 255] = 0; }
+  if (tid < R) { st_key[tid] = 0; st_cnt[tid] = 0; st_mass[tid] = 0; }
   __syncthreads();
 
   // ---- Sbar = Qbar Kbar^T * scale: fp32 pooled values, fp64 accumulation, rounded once to fp32
   float s[R][JJ];
   const float* kt = a.kbar_t + (int64_t)bh * d * a.TnP;
 #pragma unroll
-  for (int jj = 0; jj < JJ; ++jj) {
-    const int j = tid + 256 * jj;
-    double acc[R];
+  for (int jg = 0; jg < JJ; jg += G) {
+    double acc[R][G];
 #pragma unroll
-    for (int r = 0; r < R; ++r) acc[r] = 0.0;
-    if (j < Tn) {
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+      for (int u = 0; u < G; ++u) acc[r][u] = 0.0;
+    if (tid + 256 * jg < Tn) {       // whole groups past the end of the row are skipped
       for (int c = 0; c < d; ++c) {
-        const double kv = (double)kt[(int64_t)c * a.TnP + j];
+        double q4[R];
 #pragma unroll
-        for (int r = 0; r < R; ++r) acc[r] = fma(qd[r][c], kv, acc[r]);
+        for (int r = 0; r < R; ++r) q4[r] = qd[c][r];
+#pragma unroll
+        for (int u = 0; u < G; ++u) {
+          const int j = tid + 256 * (jg + u);
+          const double kv = (double)kt[(int64_t)c * a.TnP + min(j, Tn - 1)];
+#pragma unroll
+          for (int r = 0; r < R; ++r) acc[r][u] = fma(q4[r], kv, acc[r][u]);
+        }
       }
     }
 #pragma unroll
-    for (int r = 0; r < R; ++r) s[r][jj] = j < Tn ? (float)(acc[r] * (double)a.scale) : -INFINITY;
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+      for (int u = 0; u < G; ++u)
+        s[r][jg + u] = (tid + 256 * (jg + u)) < Tn ? (float)(acc[r][u] * (double)a.scale) : -INFINITY;
   }
 
   // ---- Pbar = softmax(Sbar) per row, fp32
@@ -195,70 +233,103 @@ __global__ __launch_bounds__(256) void select_kernel(SelArgs a) {
 #pragma unroll
     for (int jj = 0; jj < JJ; ++jj) {
       const int j = tid + 256 * jj;
-      uint64_t key = 0;                                   // padding sorts last
       if (j < Tn) {
         const float p = s[r][jj] / tot;
+        s[r][jj] = p;                      // from here on s holds Pbar
         if (a.pbar_out && r < nrows) a.pbar_out[((int64_t)bh * a.Tm + i0 + r) * Tn + j] = p;
-        // larger Pbar first; equal Pbar: lower block index first
-        key = ((uint64_t)__builtin_bit_cast(uint32_t, p) << 32) | (uint64_t)(0xffffffffu - (uint32_t)j);
       }
-      keys[r * NP + j] = key;
-    }
-  }
-  __syncthreads();
-
-  // ---- bitonic sort of each row, descending
-  for (int k = 2; k <= NP; k <<= 1) {
-    for (int st = k >> 1; st > 0; st >>= 1) {
-#pragma unroll
-      for (int e = 0; e < E / 2; ++e) {
-        const int pr = tid + 256 * e;
-        const int lo = 2 * st * (pr / st) + (pr % st);
-        const int hi = lo + st;
-        const bool desc = ((lo & (NP - 1)) & k) == 0;
-        const uint64_t x = keys[lo], y = keys[hi];
-        if ((x < y) == desc) { keys[lo] = y; keys[hi] = x; }
-      }
-      __syncthreads();
     }
   }
 
-  // ---- cumulative probability in sorted order (fp64), n_p, n
-  const int seg = tid / SEG_T;                    // which row this thread scans
-  const int pos0 = (tid % SEG_T) * E;             // first sorted position (within the row) of this thread
-  double excl[E];
-  double run = 0.0;
+  // ---- radix descent for the threshold key of each row
+  const uint32_t kc = (uint32_t)max(1, a.k_cnt);
+  uint64_t p_fx = fixed62(__builtin_bit_cast(uint32_t, a.top_p));
+  if (a.top_p > 0.f && p_fx == 0) p_fx = 1;
+#pragma unroll 1
+  for (int pass = 0; pass < 6; ++pass) {
+    const int sh = pass < 4 ? 56 - 8 * pass : (pass == 4 ? 8 : 0);
+    // accumulate: entries that match the prefix found so far
 #pragma unroll
-  for (int e = 0; e < E; ++e) {
-    excl[e] = run;
-    run += (double)__builtin_bit_cast(float, (uint32_t)(keys[seg * NP + pos0 + e] >> 32));
-  }
-  double seg_tot_d;
-  const double pre = segment_scan<double>(run, tid, SEG_T, sm4d, seg_tot_d);
-  int below = 0;   // positions r (0-based) whose preceding sum c_r is still < top_p
-  const double pth = (double)a.top_p;
+    for (int r = 0; r < R; ++r) {
+      const uint64_t pre = st_key[r];
 #pragma unroll
-  for (int e = 0; e < E; ++e)
-    if (pos0 + e < Tn && (pre + excl[e]) < pth) ++below;
-  int n_p;
-  segment_scan<int>(below, tid, SEG_T, sm4i, n_p);
-  if ((tid % SEG_T) == 0) {
-    int n = max(max(1, a.k_cnt), n_p);
-    n_sel[seg] = min(n, Tn);
-  }
-  __syncthreads();
-  {
-    const int n = n_sel[seg];
-#pragma unroll
-    for (int e = 0; e < E; ++e)
-      if (pos0 + e < n) {
-        const uint32_t j = 0xffffffffu - (uint32_t)(keys[seg * NP + pos0 + e] & 0xffffffffu);
-        flag[seg * NP + j] = 1;
+      for (int jj = 0; jj < JJ; ++jj) {
+        const int j = tid + 256 * jj;
+        if (j < Tn) {
+          const uint32_t fb = __builtin_bit_cast(uint32_t, s[r][jj]);
+          const uint64_t key = ((uint64_t)fb << 32) | (uint64_t)(0xffffffffu - (uint32_t)j);
+          const bool match = pass == 0 ? true : (((key ^ pre) >> (sh + 8)) == 0);
+          if (match) {
+            const int dig = (int)((key >> sh) & 255u);
+            atomicAdd(&h_cnt[r][dig], 1u);
+            atomicAdd((unsigned long long*)&h_mass[r][dig], (unsigned long long)fixed62(fb));
+          }
+        }
       }
+    }
+    __syncthreads();
+    // scan: wave r walks the bins of row r from the top; lane l owns bins 255-4l .. 252-4l
+    {
+      const int r = w;
+      uint32_t c4[4]; uint64_t m4[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int bin = 255 - 4 * lane - e;
+        c4[e] = h_cnt[r][bin]; m4[e] = h_mass[r][bin];
+        h_cnt[r][bin] = 0; h_mass[r][bin] = 0;         // ready for the next pass
+      }
+      uint32_t ct = c4[0] + c4[1] + c4[2] + c4[3];
+      uint64_t mt = m4[0] + m4[1] + m4[2] + m4[3];
+      uint32_t ci = ct; uint64_t mi = mt;                // inclusive scan over lanes (lane 0 = highest bins)
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t cy = __shfl_up(ci, off, 64);
+        const uint64_t my = __shfl_up(mi, off, 64);
+        if (lane >= off) { ci += cy; mi += my; }
+      }
+      uint32_t c_above = st_cnt[r] + (ci - ct);          // entries above this lane's first bin
+      uint64_t m_above = st_mass[r] + (mi - mt);
+      int sel_bin = -1; uint32_t sel_c = 0; uint64_t sel_m = 0;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        if (c4[e] != 0 && (c_above < kc || m_above < p_fx)) { sel_bin = 255 - 4 * lane - e; sel_c = c_above; sel_m = m_above; }
+        c_above += c4[e]; m_above += m4[e];
+      }
+      const uint64_t bal = __builtin_amdgcn_ballot_w64(sel_bin >= 0);
+      // the predicate is monotone, so the selected bins are a prefix of the walk; the last one is the boundary.
+      // (bal is never zero: the top non-empty bin always qualifies because cnt_gt of its top entry is below kc
+      // on the first pass and the boundary bin's top entry qualifies on later passes.)
+      const int src = bal ? 63 - __builtin_clzll(bal) : 0;
+      const int b_bin = __shfl(sel_bin, src, 64);
+      const uint32_t b_c = __shfl(sel_c, src, 64);
+      const uint64_t b_m = __shfl(sel_m, src, 64);
+      if (lane == 0) {
+        uint64_t key = st_key[r] | ((uint64_t)(uint32_t)max(b_bin, 0) << sh);
+        if (pass == 3) key |= 0xffff0000ull;             // bits 31..16 of every key are ones (block index < 65536)
+        st_key[r] = key; st_cnt[r] = b_c; st_mass[r] = b_m;
+      }
+    }
+    __syncthreads();
+  }
+
+  // ---- flags: key >= threshold
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const uint64_t thr = st_key[r];
+#pragma unroll
+    for (int jj = 0; jj < JJ; ++jj) {
+      const int j = tid + 256 * jj;
+      if (j < Tn) {
+        const uint64_t key = ((uint64_t)__builtin_bit_cast(uint32_t, s[r][jj]) << 32) | (uint64_t)(0xffffffffu - (uint32_t)j);
+        if (key >= thr) flag[r * NP + j] = 1;
+      }
+    }
   }
   __syncthreads();
 
   // ---- mask row and ascending index list
+  const int seg = tid / SEG_T;                    // which row this thread compacts
+  const int pos0 = (tid % SEG_T) * E;             // first block index handled by this thread
   int cntl = 0;
 #pragma unroll
   for (int e = 0; e < E; ++e) cntl += flag[seg * NP + pos0 + e];
@@ -277,7 +348,7 @@ __global__ __launch_bounds__(256) void select_kernel(SelArgs a) {
         if (f) irow[wr++] = j;
       }
     }
-    if ((tid % SEG_T) == 0) a.row_cnt[row] = n_sel[seg];
+    if ((tid % SEG_T) == 0) a.row_cnt[row] = seg_tot_i;
   }
 }
 
@@ -300,8 +371,8 @@ hipError_t launch_select(const float* qbar, const float* kbar, const Dims& m, in
   else if (m.Tn <= 512)  launch_select_t<512, 4>(a, BH, stream);
   else if (m.Tn <= 1024) launch_select_t<1024, 4>(a, BH, stream);
   else if (m.Tn <= 2048) launch_select_t<2048, 4>(a, BH, stream);
-  else if (m.Tn <= 4096) launch_select_t<4096, 2>(a, BH, stream);
-  else                   launch_select_t<8192, 1>(a, BH, stream);
+  else if (m.Tn <= 4096) launch_select_t<4096, 4>(a, BH, stream);
+  else                   launch_select_t<8192, 4>(a, BH, stream);
   return hipGetLastError();
 }
 
@@ -319,10 +390,48 @@ __global__ __launch_bounds__(256) void columns_kernel(const uint8_t* mask, int T
   col_cnt[(int64_t)bh * Tn + j] = c;
 }
 
+// Launch order of the key blocks of one head for the dK/dV kernel: longest column first, dealt round-robin
+// to the eight XCD chunks of the schedule (position x*chunk + s belongs to XCD x), so that every XCD gets the
+// same mix of long and short columns and the long ones start early.  One workgroup per head.
+template <int NP>
+__global__ __launch_bounds__(256) void col_order_kernel(const int32_t* col_cnt, int Tn, int32_t* col_order) {
+  __shared__ uint32_t keys[NP];
+  const int bh = blockIdx.x, tid = threadIdx.x;
+  for (int j = tid; j < NP; j += 256)
+    keys[j] = j < Tn ? ((uint32_t)min(col_cnt[(int64_t)bh * Tn + j], 0xffff) << 16) | (uint32_t)(0xffff - j) : 0u;
+  __syncthreads();
+  for (int k = 2; k <= NP; k <<= 1)
+    for (int st = k >> 1; st > 0; st >>= 1) {
+      for (int pr = tid; pr < NP / 2; pr += 256) {
+        const int lo = 2 * st * (pr / st) + (pr % st), hi = lo + st;
+        const bool desc = (lo & k) == 0;
+        const uint32_t x = keys[lo], y = keys[hi];
+        if ((x < y) == desc) { keys[lo] = y; keys[hi] = x; }
+      }
+      __syncthreads();
+    }
+  const int chunk = (Tn + 7) / 8;
+  for (int pos = tid; pos < Tn; pos += 256) {
+    const int x = pos / chunk, sidx = pos % chunk;
+    int rank = 0;                                  // how many schedule positions are dealt before this one
+    for (int xx = 0; xx < 8; ++xx) {
+      const int len = min(max(Tn - xx * chunk, 0), chunk);
+      rank += min(len, sidx) + ((xx < x && sidx < len) ? 1 : 0);
+    }
+    col_order[(int64_t)bh * Tn + pos] = 0xffff - (int)(keys[rank] & 0xffffu);
+  }
+}
+
 hipError_t launch_columns(const uint8_t* mask, const Dims& m, int32_t* col_cnt, int32_t* col_idx,
-                          hipStream_t stream) {
+                          int32_t* col_order, hipStream_t stream) {
   const dim3 grid((unsigned)((m.Tn + 255) / 256), (unsigned)(m.B * m.H)), block(256);
   hipLaunchKernelGGL(columns_kernel, grid, block, 0, stream, mask, m.Tm, m.Tn, col_cnt, col_idx);
+  if (col_order) {
+    const dim3 g2((unsigned)(m.B * m.H));
+    if (m.Tn <= 512)       hipLaunchKernelGGL(col_order_kernel<512>, g2, block, 0, stream, col_cnt, m.Tn, col_order);
+    else if (m.Tn <= 2048) hipLaunchKernelGGL(col_order_kernel<2048>, g2, block, 0, stream, col_cnt, m.Tn, col_order);
+    else                   hipLaunchKernelGGL(col_order_kernel<8192>, g2, block, 0, stream, col_cnt, m.Tn, col_order);
+  }
   return hipGetLastError();
 }
 
@@ -336,20 +445,24 @@ __global__ __launch_bounds__(256) void full_rows_kernel(int Tm, int Tn, uint8_t*
   }
   if (threadIdx.x == 0) row_cnt[row] = Tn;
 }
-__global__ __launch_bounds__(256) void full_cols_kernel(int Tm, int Tn, int32_t* col_cnt, int32_t* col_idx) {
+__global__ __launch_bounds__(256) void full_cols_kernel(int Tm, int Tn, int32_t* col_cnt, int32_t* col_idx,
+                                                        int32_t* col_order) {
   const int64_t colr = blockIdx.x;  // bh * Tn + j
   for (int i = threadIdx.x; i < Tm; i += 256) col_idx[colr * Tm + i] = i;
-  if (threadIdx.x == 0) col_cnt[colr] = Tm;
+  if (threadIdx.x == 0) {
+    col_cnt[colr] = Tm;
+    if (col_order) col_order[colr] = (int32_t)(colr % Tn);
+  }
 }
 
 hipError_t launch_pattern_full(const Dims& m, uint8_t* mask, int32_t* row_cnt, int32_t* row_idx,
-                               int32_t* col_cnt, int32_t* col_idx, hipStream_t stream) {
+                               int32_t* col_cnt, int32_t* col_idx, int32_t* col_order, hipStream_t stream) {
   const int BH = m.B * m.H;
   hipLaunchKernelGGL(full_rows_kernel, dim3((unsigned)(BH * m.Tm)), dim3(256), 0, stream, m.Tm, m.Tn, mask,
                      row_cnt, row_idx);
   if (col_cnt)
     hipLaunchKernelGGL(full_cols_kernel, dim3((unsigned)(BH * m.Tn)), dim3(256), 0, stream, m.Tm, m.Tn, col_cnt,
-                       col_idx);
+                       col_idx, col_order);
   return hipGetLastError();
 }
 

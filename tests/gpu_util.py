@@ -98,6 +98,10 @@ def check_pattern_consistency(pat: spa2.Pattern):
             for h in range(H):
                 for j in range(Tn):
                     assert np.array_equal(col_idx[b, h, j, :col_cnt[b, h, j]], np.flatnonzero(mask[b, h, :, j]))
+    if pat.col_order is not None:
+        order = pat.col_order.cpu().numpy()
+        assert np.array_equal(np.sort(order, axis=-1), np.broadcast_to(np.arange(Tn), order.shape)), \
+            "col_order must be a permutation of the key blocks"
     return mask
 
 

@@ -166,6 +166,28 @@ def test_strided_layout_bnhd():
     assert_close("dV", f64(dv), r_dv)
 
 
+def test_launch_orders_do_not_change_results():
+    """row_order / col_order only permute which workgroup does which block."""
+    w = _small("ord", 3000, 128, kind="lowrank", H=2)
+    q, k, v, do = (t.to(dev()) for t in wl.make_inputs(w, seed=9))
+    pat, _ = gpu_mask(q, k, 4, 0.7)
+    assert pat.col_order is not None
+    o1, lse1 = gpu_fwd(q, k, v, pat)
+    g1 = gpu_bwd(q, k, v, o1, do, lse1, pat)
+    plain = spa2.Pattern(pat.mask, pat.row_cnt, pat.row_idx, pat.col_cnt, pat.col_idx, None, None)
+    o2, lse2 = gpu_fwd(q, k, v, plain)
+    g2 = gpu_bwd(q, k, v, o2, do, lse2, plain)
+    gen = torch.Generator().manual_seed(0)
+    perm_r = torch.stack([torch.randperm(w.Tm, generator=gen) for _ in range(w.B * w.H)]).view(w.B, w.H, w.Tm)
+    perm_c = torch.stack([torch.randperm(w.Tn, generator=gen) for _ in range(w.B * w.H)]).view(w.B, w.H, w.Tn)
+    shuffled = spa2.Pattern(pat.mask, pat.row_cnt, pat.row_idx, pat.col_cnt, pat.col_idx,
+                            perm_r.int().to(dev()), perm_c.int().to(dev()))
+    o3, lse3 = gpu_fwd(q, k, v, shuffled)
+    g3 = gpu_bwd(q, k, v, o3, do, lse3, shuffled)
+    for a, b, c in zip((o1, lse1, *g1), (o2, lse2, *g2), (o3, lse3, *g3)):
+        assert torch.equal(a, b) and torch.equal(a, c)
+
+
 def test_kernels_are_deterministic():
     w = _small("det", 1500, 128, kind="lowrank", H=2)
     q, k, v, do = (t.to(dev()) for t in wl.make_inputs(w, seed=7))
