@@ -95,7 +95,7 @@ def main():
     w = wl.CONFIGS[args.workload]
     scale = 1.0 / math.sqrt(w.d)
     q, k, v, do = wl.make_inputs(w, seed=args.seed, device=dev, need_do=True)
-    o = torch.empty_like(q); dq = torch.empty_like(q); dk = torch.empty_like(q); dv = torch.empty_like(q)
+    o = torch.empty_like(q); o_res = torch.empty_like(q); dq = torch.empty_like(q); dk = torch.empty_like(q); dv = torch.empty_like(q)
     lse = torch.empty((w.B, w.H, w.N), dtype=torch.float32, device=dev)
     pat = spa2.alloc_pattern(w.B, w.H, w.N, dev)
     ws_m = torch.empty(spa2.spa2_mask_workspace_bytes(q), dtype=torch.uint8, device=dev)
@@ -112,8 +112,8 @@ def main():
         spa2.spa2_mask_pool(q, k, ws_m); mark(1)
         spa2.spa2_mask_select(q, k_cnt, w.top_p, scale, p, None, ws_m); mark(2)
         spa2.spa2_mask_columns(q, p); mark(3)
-        spa2.spa2_fwd(q, k, v, p, scale, o, lse); mark(4)
-        spa2.spa2_bwd_delta(o, do, ws_b); mark(5)
+        spa2.spa2_fwd(q, k, v, p, scale, o, lse, o_res); mark(4)
+        spa2.spa2_bwd_delta(o, do, ws_b, o_res); mark(5)
         spa2.spa2_bwd_dkdv(q, k, v, do, lse, p, scale, dk, dv, ws_b); mark(6)
         spa2.spa2_bwd_dq(q, k, v, do, lse, p, scale, dq, ws_b); mark(7)
 
@@ -148,7 +148,7 @@ def main():
                         "executed_tflops": 6.0 * units * w.d / stage_ms["dq"] / 1e9},
     }
     pool_bytes = 2.0 * w.B * w.H * w.N * w.d * 2
-    delta_bytes = 2.0 * w.B * w.H * w.N * w.d * 2 + 4.0 * w.B * w.H * w.N
+    delta_bytes = 3.0 * w.B * w.H * w.N * w.d * 2 + 4.0 * w.B * w.H * w.N      # O, O residual, dO; D
     hbm = {
         "spa2_mask_pool": {"ms": stage_ms["pool"], "alg_gbs": pool_bytes / stage_ms["pool"] / 1e6},
         "spa2_bwd_delta": {"ms": stage_ms["delta"], "alg_gbs": delta_bytes / stage_ms["delta"] / 1e6},
@@ -172,8 +172,8 @@ def main():
         spa2.spa2_pattern_full(q, full)
 
         def dense_step():
-            spa2.spa2_fwd(q, k, v, full, scale, o, lse)
-            spa2.spa2_bwd(q, k, v, o, do, lse, full, scale, dq, dk, dv, ws_b)
+            spa2.spa2_fwd(q, k, v, full, scale, o, lse, o_res)
+            spa2.spa2_bwd(q, k, v, o, do, lse, full, scale, dq, dk, dv, ws_b, o_res)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         e0.record()

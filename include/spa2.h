@@ -129,27 +129,31 @@ int spa2_pattern_full(const spa2_shape* shape, spa2_pattern* out, void* stream);
 /* Alg. 1 steps 7-21.  For every query block i, over the key blocks j listed in
  * pattern->row_idx only: S_ij = Q_i K_j^T * scale, running row maximum and sum,
  * O_i accumulated in fp32 and divided by the final sum.
- *   o    bf16 token tensor (written);  lse fp32 [B,H,N] = log sum_j exp(S) per row (written).
- * Reads pattern->row_cnt / row_idx. */
+ *   o      bf16 token tensor (written);  lse fp32 [B,H,N] = log sum_j exp(S) per row (written).
+ *   o_res  optional (NULL = not wanted) bf16 token tensor, same layout as o: the part of the fp32
+ *          result that the rounding of o to bf16 dropped, o_res = bf16(O_fp32 - o).  The backward pass
+ *          uses o + o_res for D = rowsum(dO * O); with o alone, the 2^-9 relative rounding of O is the
+ *          largest error term of dQ when |K| is large.
+ * Reads pattern->row_cnt / row_idx (and row_order if set). */
 int spa2_fwd(const void* q, const void* k, const void* v, const spa2_shape* shape,
-             const spa2_pattern* pattern, float scale, void* o, float* lse, void* stream);
+             const spa2_pattern* pattern, float scale, void* o, void* o_res, float* lse, void* stream);
 
 /* Backward of spa2_fwd for upstream gradient d_o, mask held constant.  With
  * P = exp(S - lse) on selected tiles:  dV = P^T dO,  dP = dO V^T,
  * D = rowsum(dO * O),  dS = P * (dP - D),  dQ = dS K * scale,  dK = dS^T Q * scale.
  *   dq, dk, dv  bf16 token tensors (written everywhere, zeros where no tile contributes).
  * Reads row_* (dQ) and col_* (dK, dV) of the pattern; workspace holds D. */
-int spa2_bwd(const void* q, const void* k, const void* v, const void* o, const void* d_o,
-             const float* lse, const spa2_shape* shape, const spa2_pattern* pattern, float scale,
-             void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes, void* stream);
+int spa2_bwd(const void* q, const void* k, const void* v, const void* o, const void* o_res /* or NULL */,
+             const void* d_o, const float* lse, const spa2_shape* shape, const spa2_pattern* pattern,
+             float scale, void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes, void* stream);
 
 /* The three stages of spa2_bwd, callable one by one (spa2_bwd is exactly their sequence; a caller
  * that needs only dQ, or only dK and dV, skips the other):
- *   spa2_bwd_delta  D = rowsum(dO * O), fp32 [B,H,N], left in `workspace`;
+ *   spa2_bwd_delta  D = rowsum(dO * (o + o_res)), fp32 [B,H,N], left in `workspace`;
  *   spa2_bwd_dkdv   dK, dV: one pass per key block over the query blocks listed in col_idx;
  *   spa2_bwd_dq     dQ: one pass per query block over the key blocks listed in row_idx.
  * dkdv and dq read D from `workspace` (written by spa2_bwd_delta for the same o, d_o). */
-int spa2_bwd_delta(const void* o, const void* d_o, const spa2_shape* shape,
+int spa2_bwd_delta(const void* o, const void* o_res /* or NULL */, const void* d_o, const spa2_shape* shape,
                    void* workspace, size_t workspace_bytes, void* stream);
 int spa2_bwd_dkdv(const void* q, const void* k, const void* v, const void* d_o, const float* lse,
                   const spa2_shape* shape, const spa2_pattern* pattern, float scale,

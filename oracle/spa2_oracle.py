@@ -209,17 +209,19 @@ def attention_definition(q, k, v, mbar, scale: float | None = None,
 
 
 def attention_gather(q, k, v, mbar, scale: float | None = None,
-                     bq: int = BQ, bkv: int = BKV):
+                     bq: int = BQ, bkv: int = BKV, q_blocks=None):
     """Same map, evaluated per query block on the gathered selected K/V blocks
     only (exact, not an approximation; this is the form that scales to long
-    sequences).  Returns (O [N,d], LSE [N])."""
+    sequences).  Returns (O [N,d], LSE [N]).  With `q_blocks` (an iterable of
+    query-block indices) only those blocks are evaluated and the other rows of
+    the outputs stay zero: used to spot-check very long sequences."""
     q = np.asarray(q, np.float64); k = np.asarray(k, np.float64); v = np.asarray(v, np.float64)
     n, d = q.shape
     if scale is None:
         scale = 1.0 / math.sqrt(d)
     o = np.zeros((n, d), np.float64)
     lse = np.zeros((n,), np.float64)
-    for i in range(mbar.shape[0]):
+    for i in (range(mbar.shape[0]) if q_blocks is None else q_blocks):
         r0, r1 = i * bq, min(n, (i + 1) * bq)
         cols = np.concatenate([np.arange(j * bkv, min(n, (j + 1) * bkv))
                                for j in np.flatnonzero(mbar[i])])
@@ -289,9 +291,12 @@ def attention_bwd_definition(q, k, v, mbar, d_o, scale: float | None = None,
 
 
 def attention_bwd_gather(q, k, v, mbar, d_o, scale: float | None = None,
-                         bq: int = BQ, bkv: int = BKV):
+                         bq: int = BQ, bkv: int = BKV, q_blocks=None):
     """Same gradients, per query block on the selected K/V blocks only.
-    Returns (dQ, dK, dV, O, LSE)."""
+    Returns (dQ, dK, dV, O, LSE).  With `q_blocks` only those query blocks are
+    visited: their rows of dQ, O, LSE are complete, and dK, dV hold the
+    contributions of those blocks only (complete for a key block whose whole
+    column of the mask is listed)."""
     q = np.asarray(q, np.float64); k = np.asarray(k, np.float64); v = np.asarray(v, np.float64)
     d_o = np.asarray(d_o, np.float64)
     n, d = q.shape
@@ -299,7 +304,7 @@ def attention_bwd_gather(q, k, v, mbar, d_o, scale: float | None = None,
         scale = 1.0 / math.sqrt(d)
     o = np.zeros((n, d)); lse = np.zeros((n,))
     dq = np.zeros((n, d)); dk = np.zeros((n, d)); dv = np.zeros((n, d))
-    for i in range(mbar.shape[0]):
+    for i in (range(mbar.shape[0]) if q_blocks is None else q_blocks):
         r0, r1 = i * bq, min(n, (i + 1) * bq)
         cols = np.concatenate([np.arange(j * bkv, min(n, (j + 1) * bkv))
                                for j in np.flatnonzero(mbar[i])])

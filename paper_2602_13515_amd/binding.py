@@ -69,9 +69,9 @@ def _load():
     lib.spa2_pattern_full.restype = ctypes.c_int
     lib.spa2_pattern_full.argtypes = [shp, pat, vp]
     lib.spa2_fwd.restype = ctypes.c_int
-    lib.spa2_fwd.argtypes = [vp, vp, vp, shp, pat, f32, vp, vp, vp]
+    lib.spa2_fwd.argtypes = [vp, vp, vp, shp, pat, f32, vp, vp, vp, vp]
     lib.spa2_bwd.restype = ctypes.c_int
-    lib.spa2_bwd.argtypes = [vp, vp, vp, vp, vp, vp, shp, pat, f32, vp, vp, vp, vp, sz, vp]
+    lib.spa2_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, shp, pat, f32, vp, vp, vp, vp, sz, vp]
     lib.spa2_mask_pool.restype = ctypes.c_int
     lib.spa2_mask_pool.argtypes = [vp, vp, shp, vp, sz, vp]
     lib.spa2_mask_select.restype = ctypes.c_int
@@ -79,7 +79,7 @@ def _load():
     lib.spa2_mask_columns.restype = ctypes.c_int
     lib.spa2_mask_columns.argtypes = [shp, pat, vp]
     lib.spa2_bwd_delta.restype = ctypes.c_int
-    lib.spa2_bwd_delta.argtypes = [vp, vp, shp, vp, sz, vp]
+    lib.spa2_bwd_delta.argtypes = [vp, vp, vp, shp, vp, sz, vp]
     lib.spa2_bwd_dkdv.restype = ctypes.c_int
     lib.spa2_bwd_dkdv.argtypes = [vp, vp, vp, vp, vp, shp, pat, f32, vp, vp, vp, sz, vp]
     lib.spa2_bwd_dq.restype = ctypes.c_int
@@ -193,22 +193,24 @@ def spa2_pattern_full(like: torch.Tensor, out: Pattern) -> None:
 
 
 def spa2_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, pattern: Pattern, scale: float,
-             o: torch.Tensor, lse: torch.Tensor) -> None:
-    _same_layout(q, k, v, o)
+             o: torch.Tensor, lse: torch.Tensor, o_res: Optional[torch.Tensor] = None) -> None:
+    _same_layout(q, k, v, o, *([o_res] if o_res is not None else []))
     shape = _shape_of(q)
     pat = pattern._c()
     rc = _load().spa2_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), ctypes.byref(shape), ctypes.byref(pat),
-                          float(scale), o.data_ptr(), lse.data_ptr(), _stream(q))
+                          float(scale), o.data_ptr(), o_res.data_ptr() if o_res is not None else None,
+                          lse.data_ptr(), _stream(q))
     _check(rc, "spa2_fwd")
 
 
 def spa2_bwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, o: torch.Tensor, d_o: torch.Tensor,
              lse: torch.Tensor, pattern: Pattern, scale: float, dq: torch.Tensor, dk: torch.Tensor,
-             dv: torch.Tensor, workspace: torch.Tensor) -> None:
-    _same_layout(q, k, v, o, d_o, dq, dk, dv)
+             dv: torch.Tensor, workspace: torch.Tensor, o_res: Optional[torch.Tensor] = None) -> None:
+    _same_layout(q, k, v, o, d_o, dq, dk, dv, *([o_res] if o_res is not None else []))
     shape = _shape_of(q)
     pat = pattern._c()
-    rc = _load().spa2_bwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), d_o.data_ptr(), lse.data_ptr(),
+    rc = _load().spa2_bwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(),
+                          o_res.data_ptr() if o_res is not None else None, d_o.data_ptr(), lse.data_ptr(),
                           ctypes.byref(shape), ctypes.byref(pat), float(scale), dq.data_ptr(), dk.data_ptr(),
                           dv.data_ptr(), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                           _stream(q))
@@ -242,10 +244,12 @@ def spa2_mask_columns(like: torch.Tensor, out: Pattern) -> None:
     _check(_load().spa2_mask_columns(ctypes.byref(shape), ctypes.byref(pat), _stream(like)), "spa2_mask_columns")
 
 
-def spa2_bwd_delta(o: torch.Tensor, d_o: torch.Tensor, workspace: torch.Tensor) -> None:
-    _same_layout(o, d_o)
+def spa2_bwd_delta(o: torch.Tensor, d_o: torch.Tensor, workspace: torch.Tensor,
+                   o_res: Optional[torch.Tensor] = None) -> None:
+    _same_layout(o, d_o, *([o_res] if o_res is not None else []))
     shape = _shape_of(o)
-    _check(_load().spa2_bwd_delta(o.data_ptr(), d_o.data_ptr(), ctypes.byref(shape), workspace.data_ptr(),
+    _check(_load().spa2_bwd_delta(o.data_ptr(), o_res.data_ptr() if o_res is not None else None, d_o.data_ptr(),
+                                  ctypes.byref(shape), workspace.data_ptr(),
                                   _nbytes(workspace), _stream(o)), "spa2_bwd_delta")
 
 

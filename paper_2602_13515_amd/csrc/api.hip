@@ -154,29 +154,29 @@ int spa2_pattern_full(const spa2_shape* shape, spa2_pattern* out, void* stream) 
 }
 
 int spa2_fwd(const void* q, const void* k, const void* v, const spa2_shape* shape, const spa2_pattern* pattern,
-             float scale, void* o, float* lse, void* stream) {
+             float scale, void* o, void* o_res, float* lse, void* stream) {
   int rc = check_shape(shape);
   if (rc != SPA2_OK) return rc;
   if (!q || !k || !v || !o || !lse || !pattern || !pattern->row_cnt || !pattern->row_idx) return SPA2_ERR_NULL;
-  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return SPA2_ERR_ALIGN;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(o_res)) return SPA2_ERR_ALIGN;
   if (!(scale > 0.f) || !isfinite(scale)) return SPA2_ERR_RANGE;
   const Dims m = make_dims(*shape);
-  if (launch_fwd(q, k, v, m, pattern->row_cnt, pattern->row_idx, pattern->row_order, scale, o, lse,
+  if (launch_fwd(q, k, v, m, pattern->row_cnt, pattern->row_idx, pattern->row_order, scale, o, o_res, lse,
                  (hipStream_t)stream) != hipSuccess)
     return SPA2_ERR_LAUNCH;
   return SPA2_OK;
 }
 
-int spa2_bwd_delta(const void* o, const void* d_o, const spa2_shape* shape, void* workspace,
+int spa2_bwd_delta(const void* o, const void* o_res, const void* d_o, const spa2_shape* shape, void* workspace,
                    size_t workspace_bytes, void* stream) {
   int rc = check_shape(shape);
   if (rc != SPA2_OK) return rc;
   if (!o || !d_o) return SPA2_ERR_NULL;
-  if (!aligned16(o) || !aligned16(d_o)) return SPA2_ERR_ALIGN;
+  if (!aligned16(o) || !aligned16(d_o) || !aligned16(o_res)) return SPA2_ERR_ALIGN;
   const Dims m = make_dims(*shape);
   if (!workspace || workspace_bytes < bwd_ws_bytes(m)) return SPA2_ERR_WORKSPACE;
   if (!aligned16(workspace)) return SPA2_ERR_ALIGN;
-  return launch_bwd_delta(o, d_o, m, (float*)workspace, (hipStream_t)stream) == hipSuccess ? SPA2_OK
+  return launch_bwd_delta(o, o_res, d_o, m, (float*)workspace, (hipStream_t)stream) == hipSuccess ? SPA2_OK
                                                                                            : SPA2_ERR_LAUNCH;
 }
 
@@ -213,21 +213,21 @@ int spa2_bwd_dq(const void* q, const void* k, const void* v, const void* d_o, co
                        pattern->row_order, scale, dq, (hipStream_t)stream) == hipSuccess ? SPA2_OK : SPA2_ERR_LAUNCH;
 }
 
-int spa2_bwd(const void* q, const void* k, const void* v, const void* o, const void* d_o, const float* lse,
-             const spa2_shape* shape, const spa2_pattern* pattern, float scale, void* dq, void* dk, void* dv,
-             void* workspace, size_t workspace_bytes, void* stream) {
+int spa2_bwd(const void* q, const void* k, const void* v, const void* o, const void* o_res, const void* d_o,
+             const float* lse, const spa2_shape* shape, const spa2_pattern* pattern, float scale, void* dq,
+             void* dk, void* dv, void* workspace, size_t workspace_bytes, void* stream) {
   int rc = check_shape(shape);
   if (rc != SPA2_OK) return rc;
   if (!q || !k || !v || !o || !d_o || !lse || !dq || !dk || !dv || !pattern) return SPA2_ERR_NULL;
   if (!pattern->row_cnt || !pattern->row_idx || !pattern->col_cnt || !pattern->col_idx) return SPA2_ERR_NULL;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(d_o) || !aligned16(dq) ||
-      !aligned16(dk) || !aligned16(dv))
+      !aligned16(dk) || !aligned16(dv) || !aligned16(o_res))
     return SPA2_ERR_ALIGN;
   if (!(scale > 0.f) || !isfinite(scale)) return SPA2_ERR_RANGE;
   const Dims m = make_dims(*shape);
   if (!workspace || workspace_bytes < bwd_ws_bytes(m)) return SPA2_ERR_WORKSPACE;
   if (!aligned16(workspace)) return SPA2_ERR_ALIGN;
-  rc = spa2_bwd_delta(o, d_o, shape, workspace, workspace_bytes, stream);
+  rc = spa2_bwd_delta(o, o_res, d_o, shape, workspace, workspace_bytes, stream);
   if (rc != SPA2_OK) return rc;
   rc = spa2_bwd_dkdv(q, k, v, d_o, lse, shape, pattern, scale, dk, dv, workspace, workspace_bytes, stream);
   if (rc != SPA2_OK) return rc;

@@ -17,7 +17,7 @@ namespace spa2 {
 
 // ------------------------------------------------------------------ D = rowsum(dO * O)
 struct DeltaArgs {
-  const uint16_t* o; const uint16_t* d_o; float* delta;
+  const uint16_t* o; const uint16_t* o_res; const uint16_t* d_o; float* delta;
   int H, N; int64_t sb, sh, sn;
 };
 
@@ -35,10 +35,14 @@ __global__ __launch_bounds__(256) void delta_kernel(DeltaArgs a) {
     if (row < a.N) {
       const u32x4 x = *(const u32x4*)(a.o + base + (int64_t)row * a.sn + col);
       const u32x4 y = *(const u32x4*)(a.d_o + base + (int64_t)row * a.sn + col);
+      u32x4 z = u32x4{0, 0, 0, 0};
+      if (a.o_res) z = *(const u32x4*)(a.o_res + base + (int64_t)row * a.sn + col);
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        s = fmaf(__builtin_bit_cast(float, x[e] << 16), __builtin_bit_cast(float, y[e] << 16), s);
-        s = fmaf(__builtin_bit_cast(float, x[e] & 0xffff0000u), __builtin_bit_cast(float, y[e] & 0xffff0000u), s);
+        const float o0 = __builtin_bit_cast(float, x[e] << 16) + __builtin_bit_cast(float, z[e] << 16);
+        const float o1 = __builtin_bit_cast(float, x[e] & 0xffff0000u) + __builtin_bit_cast(float, z[e] & 0xffff0000u);
+        s = fmaf(o0, __builtin_bit_cast(float, y[e] << 16), s);
+        s = fmaf(o1, __builtin_bit_cast(float, y[e] & 0xffff0000u), s);
       }
     }
 #pragma unroll
@@ -47,9 +51,10 @@ __global__ __launch_bounds__(256) void delta_kernel(DeltaArgs a) {
   }
 }
 
-hipError_t launch_bwd_delta(const void* o, const void* d_o, const Dims& m, float* delta, hipStream_t stream) {
+hipError_t launch_bwd_delta(const void* o, const void* o_res, const void* d_o, const Dims& m, float* delta,
+                            hipStream_t stream) {
   DeltaArgs a;
-  a.o = (const uint16_t*)o; a.d_o = (const uint16_t*)d_o; a.delta = delta;
+  a.o = (const uint16_t*)o; a.o_res = (const uint16_t*)o_res; a.d_o = (const uint16_t*)d_o; a.delta = delta;
   a.H = m.H; a.N = m.N; a.sb = m.sb; a.sh = m.sh; a.sn = m.sn;
   const int rows_per_wg = 4 * 256 / (m.d / 8);
   const dim3 grid((unsigned)((m.N + rows_per_wg - 1) / rows_per_wg), (unsigned)(m.B * m.H)), block(256);
@@ -278,9 +283,6 @@ struct DkvArgs {
   int64_t sb, sh, sn;
   float scale, scale_log2;
 };
-
-typedef __attribute__((address_space(1))) const void gptr_t;
-typedef __attribute__((address_space(3))) void lptr_t;
 
 // One workgroup (8 waves) per key block j (64 keys).  Wave (wq, wk) owns the 32 queries 32wq.. of the
 // current query block and the 32 keys 32wk.. of the key block; it keeps its K^T / V^T fragments and its

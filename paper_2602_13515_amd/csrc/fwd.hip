@@ -19,7 +19,7 @@ namespace spa2 {
 
 struct FwdArgs {
   const uint16_t* q; const uint16_t* k; const uint16_t* v;
-  uint16_t* o; float* lse;
+  uint16_t* o; uint16_t* o_res; float* lse;
   const int32_t* row_cnt; const int32_t* row_idx; const int32_t* row_order;
   int H, N, Tm, Tn, chunk;
   int64_t sb, sh, sn;
@@ -62,6 +62,11 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdArgs a) {
       uint16_t* op = a.o + base + (int64_t)qrow * a.sn + (D / 2) * hf;
 #pragma unroll
       for (int c = 0; c < D / 16; ++c) *(u32x4*)(op + 8 * c) = u32x4{0, 0, 0, 0};
+      if (a.o_res) {
+        uint16_t* rp = a.o_res + (op - a.o);
+#pragma unroll
+        for (int c = 0; c < D / 16; ++c) *(u32x4*)(rp + 8 * c) = u32x4{0, 0, 0, 0};
+      }
       if (hf == 0) a.lse[(int64_t)bh * N + qrow] = -INFINITY;
     }
     return;
@@ -251,20 +256,30 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdArgs a) {
     for (int mb = 0; mb < D / 32; ++mb)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        u32x2 pk2 = {pack_bf16(oacc[mb][4 * g + 0] * inv, oacc[mb][4 * g + 1] * inv),
-                     pack_bf16(oacc[mb][4 * g + 2] * inv, oacc[mb][4 * g + 3] * inv)};
+        float x[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) x[e] = oacc[mb][4 * g + e] * inv;
+        const u32x2 pk2 = {pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3])};
         *(u32x2*)(op + 32 * mb + 8 * g) = pk2;
+        if (a.o_res) {      // what the rounding to bf16 dropped, itself rounded to bf16
+          const float r0 = x[0] - __builtin_bit_cast(float, pk2[0] << 16);
+          const float r1 = x[1] - __builtin_bit_cast(float, pk2[0] & 0xffff0000u);
+          const float r2 = x[2] - __builtin_bit_cast(float, pk2[1] << 16);
+          const float r3 = x[3] - __builtin_bit_cast(float, pk2[1] & 0xffff0000u);
+          const u32x2 pr = {pack_bf16(r0, r1), pack_bf16(r2, r3)};
+          *(u32x2*)(a.o_res + (op - a.o) + 32 * mb + 8 * g) = pr;
+        }
       }
     if (hf == 0) a.lse[(int64_t)bh * N + qrow] = m_run * LN2 + __logf(l_tot);
   }
 }
 
 hipError_t launch_fwd(const void* q, const void* k, const void* v, const Dims& m, const int32_t* row_cnt,
-                      const int32_t* row_idx, const int32_t* row_order, float scale, void* o, float* lse,
-                      hipStream_t stream) {
+                      const int32_t* row_idx, const int32_t* row_order, float scale, void* o, void* o_res,
+                      float* lse, hipStream_t stream) {
   FwdArgs a;
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v;
-  a.o = (uint16_t*)o; a.lse = lse;
+  a.o = (uint16_t*)o; a.o_res = (uint16_t*)o_res; a.lse = lse;
   a.row_cnt = row_cnt; a.row_idx = row_idx; a.row_order = row_order;
   a.H = m.H; a.N = m.N; a.Tm = m.Tm; a.Tn = m.Tn;
   a.chunk = (m.Tm + 7) / 8;

@@ -14,6 +14,10 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
+// address-space qualified pointers of the direct global -> LDS copy builtin
+typedef __attribute__((address_space(1))) const void gptr_t;
+typedef __attribute__((address_space(3))) void lptr_t;
+
 constexpr int BQ = 128;
 constexpr int BKV = 64;
 constexpr float LOG2E = 1.4426950408889634f;

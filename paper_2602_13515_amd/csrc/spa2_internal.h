@@ -32,9 +32,10 @@ hipError_t launch_columns(const uint8_t* mask, const Dims& m, int32_t* col_cnt, 
 hipError_t launch_pattern_full(const Dims& m, uint8_t* mask, int32_t* row_cnt, int32_t* row_idx,
                                int32_t* col_cnt, int32_t* col_idx, int32_t* col_order, hipStream_t stream);
 hipError_t launch_fwd(const void* q, const void* k, const void* v, const Dims& m, const int32_t* row_cnt,
-                      const int32_t* row_idx, const int32_t* row_order, float scale, void* o, float* lse,
-                      hipStream_t stream);
-hipError_t launch_bwd_delta(const void* o, const void* d_o, const Dims& m, float* delta, hipStream_t stream);
+                      const int32_t* row_idx, const int32_t* row_order, float scale, void* o, void* o_res,
+                      float* lse, hipStream_t stream);
+hipError_t launch_bwd_delta(const void* o, const void* o_res, const void* d_o, const Dims& m, float* delta,
+                            hipStream_t stream);
 hipError_t launch_bwd_dq(const void* q, const void* k, const void* v, const void* d_o, const float* lse,
                          const float* delta, const Dims& m, const int32_t* row_cnt, const int32_t* row_idx,
                          const int32_t* row_order, float scale, void* dq, hipStream_t stream);

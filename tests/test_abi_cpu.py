@@ -63,16 +63,16 @@ def test_argument_validation_happens_on_the_host():
     odd = ctypes.c_void_p(0x1004)
     ok = _shape()
     f = lib.spa2_fwd
-    assert f(None, fake, fake, ctypes.byref(ok), ctypes.byref(pat), 0.1, fake, fake, None) == -1
-    assert f(fake, fake, fake, None, ctypes.byref(pat), 0.1, fake, fake, None) == -1
-    assert f(fake, fake, fake, ctypes.byref(ok), ctypes.byref(pat), 0.1, fake, fake, None) == -1   # empty pattern
+    assert f(None, fake, fake, ctypes.byref(ok), ctypes.byref(pat), 0.1, fake, None, fake, None) == -1
+    assert f(fake, fake, fake, None, ctypes.byref(pat), 0.1, fake, None, fake, None) == -1
+    assert f(fake, fake, fake, ctypes.byref(ok), ctypes.byref(pat), 0.1, fake, None, fake, None) == -1   # empty pattern
     full = binding._Pattern(0x1000, 0x1000, 0x1000, 0x1000, 0x1000)
-    assert f(odd, fake, fake, ctypes.byref(ok), ctypes.byref(full), 0.1, fake, fake, None) == -4
-    assert f(fake, fake, fake, ctypes.byref(ok), ctypes.byref(full), 0.0, fake, fake, None) == -5
-    assert f(fake, fake, fake, ctypes.byref(_shape(d=96)), ctypes.byref(full), 0.1, fake, fake, None) == -3
-    assert f(fake, fake, fake, ctypes.byref(_shape(bq=64)), ctypes.byref(full), 0.1, fake, fake, None) == -3
-    assert f(fake, fake, fake, ctypes.byref(_shape(N=0)), ctypes.byref(full), 0.1, fake, fake, None) == -2
-    assert f(fake, fake, fake, ctypes.byref(_shape(sn=132)), ctypes.byref(full), 0.1, fake, fake, None) == -4
+    assert f(odd, fake, fake, ctypes.byref(ok), ctypes.byref(full), 0.1, fake, None, fake, None) == -4
+    assert f(fake, fake, fake, ctypes.byref(ok), ctypes.byref(full), 0.0, fake, None, fake, None) == -5
+    assert f(fake, fake, fake, ctypes.byref(_shape(d=96)), ctypes.byref(full), 0.1, fake, None, fake, None) == -3
+    assert f(fake, fake, fake, ctypes.byref(_shape(bq=64)), ctypes.byref(full), 0.1, fake, None, fake, None) == -3
+    assert f(fake, fake, fake, ctypes.byref(_shape(N=0)), ctypes.byref(full), 0.1, fake, None, fake, None) == -2
+    assert f(fake, fake, fake, ctypes.byref(_shape(sn=132)), ctypes.byref(full), 0.1, fake, None, fake, None) == -4
     m = lib.spa2_mask
     big = 1 << 30
     assert m(fake, fake, ctypes.byref(ok), 1, 0.5, 0.1, ctypes.byref(full), None, None, big, None) == -6
@@ -87,7 +87,7 @@ def test_argument_validation_happens_on_the_host():
     assert m(fake, fake, ctypes.byref(ok), 1, 0.5, 0.1, ctypes.byref(half), None, fake, big, None) == -1
     b = lib.spa2_bwd
     norows = binding._Pattern(0x1000, 0x1000, 0x1000, None, None)
-    args = [fake] * 6
+    args = [fake, fake, fake, fake, None, fake, fake]
     assert b(*args, ctypes.byref(ok), ctypes.byref(norows), 0.1, fake, fake, fake, fake, big, None) == -1
     assert b(*args, ctypes.byref(ok), ctypes.byref(full), 0.1, fake, fake, fake, fake, 8, None) == -6
     assert lib.spa2_pattern_full(ctypes.byref(ok), None, None) == -1

@@ -357,3 +357,22 @@ def test_batched_wrappers_are_per_head():
     np.testing.assert_allclose(dq[0, 1], e_dq, atol=1e-12)
     np.testing.assert_allclose(dk[0, 1], e_dk, atol=1e-12)
     np.testing.assert_allclose(dv[0, 1], e_dv, atol=1e-12)
+
+
+def test_q_blocks_subset_matches_full_evaluation():
+    q, k, v, do, m = _rand_problem(700, 8, 21)
+    full = orc.attention_bwd_gather(q, k, v, m, do)
+    sub = orc.attention_bwd_gather(q, k, v, m, do, q_blocks=[1, 4])
+    for r0, r1 in ((128, 256), (512, 640)):
+        for a, b in zip((full[0], full[3], full[4]), (sub[0], sub[3], sub[4])):     # dQ, O, LSE rows
+            np.testing.assert_array_equal(a[r0:r1], b[r0:r1])
+    assert (sub[3][:128] == 0).all()
+    # a key block's gradient is complete once every query block of its column is visited
+    j = 3
+    rows = [int(i) for i in np.flatnonzero(m[:, j])]
+    part = orc.attention_bwd_gather(q, k, v, m, do, q_blocks=rows)
+    np.testing.assert_allclose(part[1][j * 64:(j + 1) * 64], full[1][j * 64:(j + 1) * 64], atol=1e-13)
+    np.testing.assert_allclose(part[2][j * 64:(j + 1) * 64], full[2][j * 64:(j + 1) * 64], atol=1e-13)
+    o_sub, lse_sub = orc.attention_gather(q, k, v, m, q_blocks=[2])
+    o_all, lse_all = orc.attention_gather(q, k, v, m)
+    np.testing.assert_array_equal(o_sub[256:384], o_all[256:384])
