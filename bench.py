@@ -36,6 +36,9 @@ def parse():
     ap.add_argument("--dense-steps", type=int, default=1, help="timed dense fwd+bwd passes (0 = skip)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="before the warm-up, run one plain device-to-device copy of this many MiB (a kernel of "
+                         "known HBM traffic against which rocprofv3's FETCH_SIZE / WRITE_SIZE are scaled)")
     return ap.parse_args()
 
 
@@ -117,6 +120,12 @@ def main():
         spa2.spa2_bwd_dkdv(q, k, v, do, lse, p, scale, dk, dv, ws_b); mark(6)
         spa2.spa2_bwd_dq(q, k, v, do, lse, p, scale, dq, ws_b); mark(7)
 
+    if args.calibration_copy_mib > 0:
+        src = torch.empty(args.calibration_copy_mib << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step(pat)
     torch.cuda.synchronize()
