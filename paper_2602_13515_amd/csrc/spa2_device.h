@@ -74,6 +74,16 @@ __device__ __forceinline__ bf16x8 join_tr(u32x2 lo, u32x2 hi) {
 __device__ __forceinline__ float other_half(float x) {
   return __shfl_xor(x, 32, 64);
 }
+// The same exchange on the vector ALU (v_permlane32_swap), without a trip through LDS: returns max / sum of
+// the values that lanes l and l^32 hold, in both lanes.
+__device__ __forceinline__ void both_halves(float x, float& lo, float& hi) {
+  const uint32_t u = __builtin_bit_cast(uint32_t, x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  lo = __builtin_bit_cast(float, (uint32_t)r[0]);
+  hi = __builtin_bit_cast(float, (uint32_t)r[1]);
+}
+__device__ __forceinline__ float max_halves(float x) { float lo, hi; both_halves(x, lo, hi); return fmaxf(lo, hi); }
+__device__ __forceinline__ float sum_halves(float x) { float lo, hi; both_halves(x, lo, hi); return lo + hi; }
 
 // acc + lo(p) + hi(p) for a packed bf16 pair p, accumulated in fp32 (v_dot2c_f32_bf16 with a pair of ones)
 __device__ __forceinline__ float dot2_ones(uint32_t p, float acc) {
