@@ -1,7 +1,8 @@
 """spa2: SpargeAttention2's hot path (hybrid Top-k+Top-p block masker, block-sparse
 attention forward and backward) as hand-written HIP kernels for AMD MI355X (gfx950).
 
-`binding` exposes the C ABI of libspa2.so one-to-one; `workloads` holds the seeded
+`binding` exposes the C ABI of libspa2.so one-to-one; `autograd` wraps the three calls into a
+differentiable operator; `workloads` holds the seeded
 synthetic input recipes; `build` compiles the library in-tree with hipcc.
 """
 from .binding import (  # noqa: F401
@@ -9,3 +10,4 @@ from .binding import (  # noqa: F401
     spa2_mask_workspace_bytes, spa2_pattern_full, spa2_mask_pool, spa2_mask_select, spa2_mask_columns,
     spa2_bwd_delta, spa2_bwd_dkdv, spa2_bwd_dq, spa2_strerror, spa2_topk_blocks, spa2_version,
 )
+from .autograd import SpargeAttn2, build_pattern, sparge_attn2  # noqa: F401,E402

@@ -154,3 +154,13 @@ def test_stress_recipe_has_uniform_and_sink_rows():
     even, odd = pbar[0::2], pbar[1::2]
     assert np.abs(even * w.Tn - 1).max() < 0.02         # near-uniform rows
     assert (odd[:, 0] > 0.5).all()                      # the sink block dominates
+
+
+def test_operator_has_no_cpu_path():
+    import torch
+    import paper_2602_13515_amd as spa2
+    x = torch.zeros((1, 1, 128, 64), dtype=torch.bfloat16)
+    with pytest.raises(ValueError):
+        spa2.sparge_attn2(x, x, x, 0.1, 0.5)
+    with pytest.raises(ValueError):
+        spa2.sparge_attn2(x.float(), x.float(), x.float(), 0.1, 0.5)

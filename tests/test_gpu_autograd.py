@@ -1,0 +1,67 @@
+"""The differentiable operator (Sec. 4.3: O = SpargeAttn2(Q, K, V, k%, p%)) against the oracle: forward output and
+the gradients that .backward() returns, on the pattern the operator itself built."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2602_13515_amd as spa2
+from oracle import spa2_oracle as orc
+from paper_2602_13515_amd import workloads as wl
+
+from gpu_util import assert_close, dev, f64
+
+pytestmark = pytest.mark.gpu
+
+
+def _oracle(q, k, v, do, mask):
+    return orc.attention_bwd_bh(f64(q), f64(k), f64(v), mask, f64(do))
+
+
+def test_operator_forward_backward_match_oracle():
+    w = wl.Workload("op", 1, 2, 700, 64, 0.25, 0.7, "gaussian", True)
+    q, k, v, do = (t.to(dev()) for t in wl.make_inputs(w, seed=3))
+    qg, kg, vg = (t.clone().requires_grad_(True) for t in (q, k, v))
+    o, pat = spa2.sparge_attn2(qg, kg, vg, w.k_frac, w.top_p, return_pattern=True)
+    (o.float() * do.float()).sum().backward()
+    torch.cuda.synchronize()
+    mask = pat.mask.cpu().numpy()
+    # the operator's pattern is the masker's: every row keeps at least k_cnt blocks
+    assert int(pat.row_cnt.min()) >= spa2.spa2_topk_blocks(w.k_frac, w.Tn)
+    r_dq, r_dk, r_dv, r_o, _ = _oracle(q, k, v, do, mask)
+    assert_close("O", f64(o), r_o)
+    assert_close("dQ", f64(qg.grad), r_dq); assert_close("dK", f64(kg.grad), r_dk); assert_close("dV", f64(vg.grad), r_dv)
+    assert qg.grad.dtype == torch.bfloat16 and qg.grad.shape == q.shape
+
+
+def test_operator_takes_token_major_layout_and_mixed_strides():
+    """[B, N, H, d] activations passed as permuted views; v arrives with other strides than q."""
+    B, H, N, d = 2, 3, 500, 128
+    g = torch.Generator().manual_seed(5)
+    x = torch.randn((B, N, 2, H, d), generator=g).bfloat16().to(dev())       # fused q/k projection output
+    q = x[:, :, 0].permute(0, 2, 1, 3).detach().requires_grad_(True)
+    k = x[:, :, 1].permute(0, 2, 1, 3).detach().requires_grad_(True)
+    v = torch.randn((B, H, N, d), generator=g).bfloat16().to(dev()).requires_grad_(True)   # head-major
+    do = torch.randn((B, H, N, d), generator=g).bfloat16().to(dev())
+    attn = spa2.SpargeAttn2(k_frac=0.3, top_p=0.5)
+    o = attn(q, k, v)
+    assert o.shape == (B, H, N, d) and o.stride() == q.stride()
+    o.backward(do)
+    torch.cuda.synchronize()
+    pat = spa2.build_pattern(q.detach(), k.detach(), 0.3, 0.5)
+    r_dq, r_dk, r_dv, r_o, _ = _oracle(q.detach(), k.detach(), v.detach(), do, pat.mask.cpu().numpy())
+    assert_close("O", f64(o.detach()), r_o)
+    assert_close("dQ", f64(q.grad), r_dq); assert_close("dK", f64(k.grad), r_dk); assert_close("dV", f64(v.grad), r_dv)
+
+
+def test_operator_reuses_a_given_pattern_and_rejects_cpu_tensors():
+    w = wl.Workload("op2", 1, 1, 384, 64, 0.5, 0.5, "gaussian", True)
+    q, k, v, do = (t.to(dev()) for t in wl.make_inputs(w, seed=1))
+    full = spa2.alloc_pattern(1, 1, w.N, dev())
+    spa2.spa2_pattern_full(q, full)
+    o = spa2.sparge_attn2(q, k, v, 0.0, 0.0, pattern=full)
+    ref = torch.nn.functional.scaled_dot_product_attention(q.double().cpu(), k.double().cpu(), v.double().cpu())
+    assert_close("O dense", f64(o), ref.numpy())
+    with pytest.raises(ValueError):
+        spa2.sparge_attn2(q.cpu(), k.cpu(), v.cpu(), 0.1, 0.5)
