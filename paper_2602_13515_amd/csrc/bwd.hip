@@ -355,28 +355,78 @@ __global__ __launch_bounds__(512, 2) void dkdv_kernel(DkvArgs a) {
   // last token and get LSE = +inf, so their P and dS are exactly zero.
   // thread t fills chunk position t % CPR of rows t / CPR + r * (512 / CPR); 512 / CPR is a multiple of
   // 16 rows, so the swizzle term is the same for every r
-  // (recomputed per request from the thread id: a few integer ops instead of two live registers)
-  float stat = 0.f;                                    // LSE (threads 0..127) or D (threads 128..255) of one row
-  auto request_tile = [&](int i, int stage) {
-    i = min(max(i, 0), a.Tm - 1);
-    const int64_t tile = base + (int64_t)i * BQ * a.sn;
-    const int last = min(BQ - 1, N - 1 - i * BQ);
-    const int ld_row0 = tid / CPR;
+  float stat = 0.f;                                    // LSE (waves 0, 1) or D (waves 2, 3) of one row
+  // Everything a request needs is either wave-uniform (scalar registers) or one 32-bit lane offset:
+  // the loop body then issues the copies without vector address arithmetic and without waiting on
+  // anything (a wait on any vector-memory result would also wait for the copies queued before it).
+  const int ld_row0 = tid / CPR;
+  const uint32_t goff = (uint32_t)((ld_row0 * a.sn + (((tid % CPR) ^ swz<D>(ld_row0)) * 8)) * 2);   // bytes, r = 0
+  const uint64_t row_step = (uint64_t)(512 / CPR) * (uint64_t)a.sn * 2;                               // bytes per r
+  const char* q_head = (const char*)(a.q + base);
+  const char* o_head = (const char*)(a.d_o + base);
+  // (a pointer in the global address space: through a generic one the load below could alias LDS and
+  // would have to wait for the copies queued before it)
+  typedef const __attribute__((address_space(1))) float* gfloat_ptr;
+  gfloat_ptr stat_src;
+  {
+    const uint64_t sp = (uint64_t)((w < 2 ? a.lse : a.delta) + (int64_t)bh * N);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)sp), hi = __builtin_amdgcn_readfirstlane((uint32_t)(sp >> 32));
+    stat_src = (gfloat_ptr)(((uint64_t)hi << 32) | lo);
+  }
+  // the index list, 64 entries at a time in one register (lane l holds entry 64c + l): reading entry t is a
+  // lane read, not a memory access
+  int idx_v = idx[min(lane, cnt - 1)];
+  auto list_entry = [&](int t) -> int {      // t uniform, inside the chunk that idx_v holds
+    return __builtin_amdgcn_readlane(idx_v, t & 63);
+  };
+  // One request = 2 * CH copy instructions per lane.  The texture unit takes them at about one
+  // 16-byte lane group per few cycles, and a wave that issues them back to back sits at the issue
+  // stage until the last one is accepted; so for a full tile they are handed out one at a time between
+  // the MFMAs of the S / dP loop (request_piece), and only the short last query block is requested in
+  // one go (request_ragged).
+  auto request_stat = [&](int i) {
+    if (w < 4) {
+      const int srow = i * BQ + (tid & (BQ - 1));
+      // (the conversion of LSE to log2 units is left to publish_stat: using the value here would make
+      // the wave wait for every copy requested before it)
+      if (srow < N) stat = stat_src[srow];
+      else          stat = w < 2 ? INFINITY : 0.f;
+    }
+  };
+  auto request_piece = [&](int i, int stage, int piece) {       // piece in [0, 2 CH): Q chunk, dO chunk, ...
+    const uint64_t tile_bytes = (uint64_t)i * BQ * (uint64_t)a.sn * 2;       // uniform
+    const int r = piece >> 1;
+    // the lane offset is made opaque here so that no per-piece 64-bit address is formed outside the loop
+    // (eight of them would be spilled): the copy then takes a scalar base plus this one 32-bit register
+    uint32_t g = goff;
+    asm volatile("" : "+v"(g));
+    const char* src = ((piece & 1) ? o_head : q_head) + tile_bytes + r * row_step + g;
+    uint16_t* dst = smem + 2 * stage * TILE + (piece & 1) * TILE + (r * 512 + w * 64) * 8;   // wave-uniform
+    __builtin_amdgcn_global_load_lds((gptr_t*)src, (lptr_t*)dst, 16, 0, 0);
+  };
+  auto request_ragged = [&](int i, int stage) {   // rows past N are clamped to the last token
+    const uint64_t tile_bytes = (uint64_t)i * BQ * (uint64_t)a.sn * 2;
+    const char* qt = q_head + tile_bytes;
+    const char* ot = o_head + tile_bytes;
+    uint16_t* dst0 = smem + 2 * stage * TILE + w * 64 * 8;
+    const int last = N - 1 - i * BQ;
     const int ld_c8 = ((tid % CPR) ^ swz<D>(ld_row0)) * 8;
 #pragma unroll
     for (int r = 0; r < CH; ++r) {
-      const int64_t off = tile + (int64_t)min(ld_row0 + r * (512 / CPR), last) * a.sn + ld_c8;
-      uint16_t* dst = smem + 2 * stage * TILE + (r * 512 + w * 64) * 8;       // wave-uniform
-      __builtin_amdgcn_global_load_lds((gptr_t*)(a.q + off), (lptr_t*)dst, 16, 0, 0);
-      __builtin_amdgcn_global_load_lds((gptr_t*)(a.d_o + off), (lptr_t*)(dst + TILE), 16, 0, 0);
+      const uint32_t o2 = (uint32_t)((min(ld_row0 + r * (512 / CPR), last) * a.sn + ld_c8) * 2);
+      uint16_t* dst = dst0 + r * 512 * 8;
+      __builtin_amdgcn_global_load_lds((gptr_t*)(qt + o2), (lptr_t*)dst, 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t*)(ot + o2), (lptr_t*)(dst + TILE), 16, 0, 0);
     }
-    if (tid < 2 * BQ) {
-      const int srow = i * BQ + (tid & (BQ - 1));
-      // (the conversion of LSE to log2 units is left to publish_stat: using the value here would make
-      // the wave wait for every copy requested above)
-      if (srow < N) stat = tid < BQ ? a.lse[(int64_t)bh * N + srow] : a.delta[(int64_t)bh * N + srow];
-      else          stat = tid < BQ ? INFINITY : 0.f;
+  };
+  auto request_tile = [&](int i, int stage) {     // everything at once (prologue)
+    if ((i + 1) * BQ <= N) {
+#pragma unroll
+      for (int piece = 0; piece < 2 * CH; ++piece) request_piece(i, stage, piece);
+    } else {
+      request_ragged(i, stage);
     }
+    request_stat(i);
   };
   auto publish_stat = [&](int stage) {
     if (tid < BQ) lse_s[stage * BQ + tid] = stat * LOG2E;
@@ -392,13 +442,21 @@ __global__ __launch_bounds__(512, 2) void dkdv_kernel(DkvArgs a) {
   int t_base0 = swz_idx<D>(wq * 32 + 4 * hf + (s16 >> 2), 16 * hb16 + 4 * (s16 & 3));
   int t_base1 = swz_idx<D>(wq * 32 + 8 + 4 * hf + (s16 >> 2), 16 * hb16 + 4 * (s16 & 3));
 
-  request_tile(idx[0], 0);
+  request_tile(min(max(list_entry(0), 0), a.Tm - 1), 0);
   publish_stat(0);
   __syncthreads();
 
   for (int t = 0; t < cnt; ++t) {
     const bool more = t + 1 < cnt;
-    if (more) request_tile(idx[t + 1], (t + 1) & 1);
+    int i_nx = 0;
+    bool piecewise = false;
+    if (more) {
+      if (((t + 1) & 63) == 0) idx_v = idx[min(t + 1 + lane, cnt - 1)];     // next 64 entries of the list
+      i_nx = min(max(list_entry(t + 1), 0), a.Tm - 1);
+      piecewise = (i_nx + 1) * BQ <= N;
+      if (!piecewise) request_ragged(i_nx, (t + 1) & 1);
+      request_stat(i_nx);
+    }
     const int st = t & 1;
     const uint16_t* Qb = smem + 2 * st * TILE;
     const uint16_t* Ob = Qb + TILE;
@@ -425,6 +483,11 @@ __global__ __launch_bounds__(512, 2) void dkdv_kernel(DkvArgs a) {
         if (kk + 2 < D / 16) fq[kk & 1] = *(const bf16x8*)(Qb + (a_base ^ ((kk + 2) << 4)));
         dp = mfma32(fo[kk & 1], vf[kk], dp);
         if (kk + 2 < D / 16) fo[kk & 1] = *(const bf16x8*)(Ob + (a_base ^ ((kk + 2) << 4)));
+        // the 2 CH copies of the next tile, one per step
+        if (piecewise) {
+#pragma unroll
+          for (int c = 0; c < (2 * CH) / (D / 16); ++c) request_piece(i_nx, (t + 1) & 1, kk * ((2 * CH) / (D / 16)) + c);
+        }
         __builtin_amdgcn_sched_barrier(0);
       }
     }
