@@ -141,16 +141,43 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdArgs a) {
   // written to LDS buffer T&1 at the start of iteration T-1 (that buffer held tile T-2, fully consumed
   // before the barrier that ended iteration T-2), and consumed in iteration T.  Two tiles are in flight
   // at any time and one barrier per tile is enough.
-  load_tile(stA, idx[0]);
+  // The list of selected key blocks is read with scalar loads, one entry per iteration and one iteration
+  // ahead of its use: jw[m] is the (clamped) block of tile t+m, jpre the entry that becomes jw[3] next.
+  auto list_at = [&](int t) -> int { return min(max(idx[min(t, cnt - 1)], 0), a.Tn - 1); };
+  int jw[4] = {list_at(0), list_at(1), list_at(2), list_at(3)};
+  int jpre = idx[min(4, cnt - 1)];      // raw: clamped when it is used, so that nothing waits for it here
+  // One piece of the staging work of an iteration: chunk r of K (p even) or V (p odd) of `next` goes to LDS
+  // buffer `buf` (tile t+1, requested two iterations ago), then the same registers request tile t+3.  The
+  // pieces are handed out between the MFMAs of the S^T loop: issued back to back, the eight requests would
+  // keep the wave at the issue stage until the texture unit has taken the last one.
+  // Both halves are unconditional (past the end of the list the last tile is requested again and the store
+  // goes to a buffer nobody reads): a branch around a memory operation inside the loop would make the
+  // compiler wait for every outstanding request at each store.
+  auto stage_piece = [&](Stage& st, int p, int buf, const char* kp, const char* vp, int last) {
+    const int r = p >> 1;
+    const uint32_t off = (uint32_t)((min(ld_row + RSTEP * r, last) * a.sn + ld_col) * 2);
+    if (p & 1) {
+      *(u32x4*)(Vs + buf * C::V_ELEMS + lds_v + RSTEP * r * C::VP) = st.v[r];
+      st.v[r] = *(const u32x4*)(vp + off);
+    } else {
+      *(u32x4*)(Ks + buf * C::K_ELEMS + lds_k + RSTEP * r * C::KP) = st.k[r];
+      st.k[r] = *(const u32x4*)(kp + off);
+    }
+  };
+  load_tile(stA, jw[0]);
   store_tile(stA, 0);
-  if (cnt > 1) load_tile(stB, idx[1]);
-  if (cnt > 2) load_tile(stA, idx[2]);
+  load_tile(stB, jw[1]);
+  load_tile(stA, jw[2]);
   __syncthreads();
 
   auto iteration = [&](int t, Stage& next, Stage& /*unused*/) {
-    const int j = min(max(idx[t], 0), a.Tn - 1);
-    if (t + 1 < cnt) store_tile(next, (t + 1) & 1);
-    if (t + 3 < cnt) load_tile(next, idx[t + 3]);
+    const int j = jw[0], j3 = jw[3];
+    const int64_t tile3 = (base + (int64_t)j3 * BKV * a.sn) * 2;       // uniform
+    const char* kp3 = (const char*)a.k + tile3;
+    const char* vp3 = (const char*)a.v + tile3;
+    const int last3 = min(BKV - 1, N - 1 - j3 * BKV);
+    jw[0] = jw[1]; jw[1] = jw[2]; jw[2] = jw[3]; jw[3] = min(max(jpre, 0), a.Tn - 1);
+    jpre = idx[min(t + 5, cnt - 1)];
     const uint16_t* Kb = Ks + (t & 1) * C::K_ELEMS;
     const uint16_t* Vb = Vs + (t & 1) * C::V_ELEMS;
 
@@ -174,6 +201,7 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdArgs a) {
           const int y = x + PD;
           kfr[x % PD] = *(const bf16x8*)(Kb + k_off + (y / (D / 16)) * 32 * C::KP + 16 * (y % (D / 16)));
         }
+        if (x % 2 == 0) stage_piece(next, x / 2, (t + 1) & 1, kp3, vp3, last3);
         __builtin_amdgcn_sched_barrier(0);
       }
     }
