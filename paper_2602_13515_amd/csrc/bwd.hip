@@ -75,9 +75,10 @@ struct DqArgs {
 
 template <int D>
 struct DqCfg {
-  static constexpr int K_ELEMS = BKV * D;      // K tile, XOR-swizzled: read along rows (S^T) and transposed (dQ^T)
-  static constexpr int VP = D + 8;             // V tile pitch (row reads for dP^T)
-  static constexpr int V_ELEMS = BKV * VP;
+  // K and V tiles, XOR-swizzled and unpadded (the layout a direct global -> LDS copy can write): K is read
+  // along rows (S^T) and transposed (dQ^T), V along rows (dP^T)
+  static constexpr int K_ELEMS = BKV * D;
+  static constexpr int V_ELEMS = BKV * D;
   static constexpr int CH = BKV * D / 8 / 256;
 };
 
@@ -88,8 +89,8 @@ struct DqCfg {
 template <int D>
 __global__ __launch_bounds__(256, 2) void dq_kernel(DqArgs a) {
   using C = DqCfg<D>;
-  __shared__ __align__(16) uint16_t Ks[2 * C::K_ELEMS];
-  __shared__ __align__(16) uint16_t Vs[2 * C::V_ELEMS];
+  __shared__ __align__(16) uint16_t smem[2 * (C::K_ELEMS + C::V_ELEMS)];   // stage s: K tile, then V tile
+  constexpr int STAGE = C::K_ELEMS + C::V_ELEMS;
 
   const HeadBlock hb = xcd_map(blockIdx.x, a.Tm, a.chunk);
   if (!hb.valid) return;
@@ -125,42 +126,21 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(DqArgs a) {
   const float lse2 = a.lse[(int64_t)bh * N + qrow_ld] * LOG2E;
   const float dlt = a.delta[(int64_t)bh * N + qrow_ld];
 
-  // K/V tile staging: same scheme as the forward kernel (rows past N clamped; their P is zero)
-  constexpr int RSTEP = 256 / (D / 8);
-  const int ld_row = tid / (D / 8), ld_col = (tid % (D / 8)) * 8;
-  uint32_t goff[C::CH];
-#pragma unroll
-  for (int r = 0; r < C::CH; ++r) goff[r] = (uint32_t)(((ld_row + RSTEP * r) * a.sn + ld_col) * 2);
-  const int lds_k = swz_idx<D>(ld_row, ld_col), lds_v = ld_row * C::VP + ld_col;   // RSTEP is a multiple of 16 rows
-  u32x4 kreg[C::CH], vreg[C::CH];
-  auto load_tile = [&](int j) {
-    j = min(max(j, 0), a.Tn - 1);
-    const int64_t tile = (base + (int64_t)j * BKV * a.sn) * 2;
-    const char* kp = (const char*)a.k + tile;
-    const char* vp = (const char*)a.v + tile;
-    if ((j + 1) * BKV <= N) {
-#pragma unroll
-      for (int r = 0; r < C::CH; ++r) {
-        kreg[r] = *(const u32x4*)(kp + goff[r]);
-        vreg[r] = *(const u32x4*)(vp + goff[r]);
-      }
-    } else {
-      const int last = N - 1 - j * BKV;
-#pragma unroll
-      for (int r = 0; r < C::CH; ++r) {
-        const uint32_t o2 = (uint32_t)((min(ld_row + RSTEP * r, last) * a.sn + ld_col) * 2);
-        kreg[r] = *(const u32x4*)(kp + o2);
-        vreg[r] = *(const u32x4*)(vp + o2);
-      }
-    }
+  // K/V tiles are copied global -> LDS directly (no staging registers).  The destination of a wave-wide
+  // 16-byte-per-lane copy is linear (wave base + 16 * lane), so the swizzle is applied on the source side: the
+  // lane that fills chunk position pc of a row fetches logical chunk pc ^ swz(row).  Thread t fills chunk
+  // position t % CPR of rows t / CPR + r * RSTEP; RSTEP is a multiple of 16 rows, so the swizzle term is the
+  // same for every r.  Rows past N (short last block) are clamped to the last token: their P is zero.
+  constexpr int CPR = D / 8, RSTEP = 256 / CPR;
+  const int ld_row = tid / CPR;
+  int ld_c8 = ((tid % CPR) ^ swz<D>(ld_row)) * 8;
+  auto copy_piece = [&](int p, int buf, const char* kp, const char* vp, int last) {   // p in [0, 2 CH)
+    const int r = p >> 1;
+    const uint32_t off = (uint32_t)((min(ld_row + RSTEP * r, last) * a.sn + ld_c8) * 2);
+    const uint16_t* dst = smem + buf * STAGE + (p & 1) * C::K_ELEMS + (r * 256 + w * 64) * 8;   // wave-uniform
+    raw_copy16_to_lds((p & 1) ? vp : kp, off, dst);
   };
-  auto store_tile = [&](int buf) {
-#pragma unroll
-    for (int r = 0; r < C::CH; ++r) {
-      *(u32x4*)(Ks + buf * C::K_ELEMS + lds_k + RSTEP * r * D) = kreg[r];
-      *(u32x4*)(Vs + buf * C::V_ELEMS + lds_v + RSTEP * r * C::VP) = vreg[r];
-    }
-  };
+  constexpr int NPIECE = 2 * C::CH;
 
   f32x16 acc[D / 32];
 #pragma unroll
@@ -168,47 +148,87 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(DqArgs a) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[mb][v] = 0.f;
 
-  // per-lane LDS offsets.  K row reads: row 32kb + r32, logical chunk 2kk + hf.
-  int k_off[D / 16];
-#pragma unroll
-  for (int kk = 0; kk < D / 16; ++kk) k_off[kk] = swz_idx<D>(r32, 16 * kk + 8 * hf);
-  const int v_off = r32 * C::VP + 8 * hf;
-  // K transposing reads: rows (16-row group) + 8*which + 4hf + (s16>>2), columns 32mb + 16hb + 4(s16&3)
+  // per-lane LDS element offsets.  K row reads: row 32kb + r32, logical chunk 2kk + hf; the part of the
+  // chunk index that depends on kk is XORed in as (kk << 4).
+  int ka_base = swz_idx<D>(r32, 8 * hf);       // the V row reads use the same offsets
+  // K transposing reads: rows (16-row group) + 8*which + 4hf + (s16>>2), columns 32mb + 16hb + 4(s16&3);
+  // the part that depends on mb is XORed in as (mb << 5)
   const int s16 = lane & 15, hb16 = (lane >> 4) & 1;
-  int kt_off[2][D / 32];
-#pragma unroll
-  for (int wh = 0; wh < 2; ++wh)
-#pragma unroll
-    for (int mb = 0; mb < D / 32; ++mb)
-      kt_off[wh][mb] = swz_idx<D>(8 * wh + 4 * hf + (s16 >> 2), 32 * mb + 16 * hb16 + 4 * (s16 & 3));
+  int kt_base0 = swz_idx<D>(4 * hf + (s16 >> 2), 16 * hb16 + 4 * (s16 & 3));
+  int kt_base1 = swz_idx<D>(8 + 4 * hf + (s16 >> 2), 16 * hb16 + 4 * (s16 & 3));
 
-  load_tile(idx[0]);
-  store_tile(0);
+  // The copies of tile t+1 are handed out between the MFMAs of the S^T / dP^T products of iteration t: issued
+  // back to back they keep the wave at the issue stage until the texture unit has taken the last one.  They are
+  // unconditional (past the end of the list the last tile is requested again, into the buffer nobody reads).
+  // the index list, 64 entries at a time in one register (lane l holds entry 64c + l): reading an entry is
+  // a lane read, not a memory access whose result the loop would have to wait for
+  int idx_v = idx[min(lane, cnt - 1)];
+  auto list_entry = [&](int t) -> int {      // t uniform, inside the chunk that idx_v holds
+    return min(max(__builtin_amdgcn_readlane(idx_v, t & 63), 0), a.Tn - 1);
+  };
+  int j_cur = list_entry(0);
+  {
+    const int64_t tile0 = (base + (int64_t)j_cur * BKV * a.sn) * 2;
+    const int last0 = min(BKV - 1, N - 1 - j_cur * BKV);
+#pragma unroll
+    for (int p = 0; p < NPIECE; ++p) copy_piece(p, 0, (const char*)a.k + tile0, (const char*)a.v + tile0, last0);
+  }
+  raw_copies_done();
   __syncthreads();
 
   for (int t = 0; t < cnt; ++t) {
-    const int j = min(max(idx[t], 0), a.Tn - 1);
-    const bool more = t + 1 < cnt;
-    if (more) load_tile(idx[t + 1]);
-    const uint16_t* Kb = Ks + (t & 1) * C::K_ELEMS;
-    const uint16_t* Vb = Vs + (t & 1) * C::V_ELEMS;
+    const int j = j_cur;
+    if (((t + 1) & 63) == 0 && t + 1 < cnt) idx_v = idx[min(t + 1 + lane, cnt - 1)];     // next 64 entries
+    const int j_nxt = list_entry(min(t + 1, cnt - 1));
+    const int64_t tile_n = (base + (int64_t)j_nxt * BKV * a.sn) * 2;      // uniform
+    const char* kpn = (const char*)a.k + tile_n;
+    const char* vpn = (const char*)a.v + tile_n;
+    const int last_n = min(BKV - 1, N - 1 - j_nxt * BKV);
+    j_cur = j_nxt;
+    const uint16_t* Kb = smem + (t & 1) * STAGE;
+    const uint16_t* Vb = Kb + C::K_ELEMS;
 
+    // keep the XORed operand addresses out of loop-invariant hoisting (one VALU op per read instead of
+    // a dozen live registers)
+    asm volatile("" : "+v"(ka_base), "+v"(kt_base0), "+v"(kt_base1), "+v"(ld_c8));
+
+    // ---- S^T and dP^T: for each 32-key block D/16 MFMAs of K Q^T, then D/16 of V dO^T.  LDS operands run
+    // PDQ MFMAs ahead of their use; request piece p of tile t+1 goes out after MFMA p * NM1 / NPIECE.
+    constexpr int NM1 = 4 * (D / 16), PDQ = 4;
+    auto frag1 = [&](int y) -> bf16x8 {
+      const int kb = y / (2 * (D / 16)), rem = y % (2 * (D / 16)), kk = rem % (D / 16);
+      return *(const bf16x8*)((rem < D / 16 ? Kb : Vb) + (ka_base ^ (kk << 4)) + kb * 32 * D);
+    };
     f32x16 s[2], dp[2];
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
+    for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int v = 0; v < 16; ++v) { s[kb][v] = 0.f; dp[kb][v] = 0.f; }
+    {
+      bf16x8 fr[PDQ];
 #pragma unroll
-      for (int kk = 0; kk < D / 16; ++kk) {
-        const bf16x8 ka = *(const bf16x8*)(Kb + k_off[kk] + kb * 32 * D);
-        s[kb] = mfma32(ka, qf[kk], s[kb]);
-      }
+      for (int x = 0; x < PDQ; ++x) fr[x] = frag1(x);
 #pragma unroll
-      for (int kk = 0; kk < D / 16; ++kk) {
-        const bf16x8 va = *(const bf16x8*)(Vb + v_off + kb * 32 * C::VP + 16 * kk);
-        dp[kb] = mfma32(va, dof[kk], dp[kb]);
+      for (int y = 0; y < NM1; ++y) {
+        const int kb = y / (2 * (D / 16)), rem = y % (2 * (D / 16)), kk = rem % (D / 16);
+        if (rem < D / 16) s[kb] = mfma32(fr[y % PDQ], qf[kk], s[kb]);
+        else              dp[kb] = mfma32(fr[y % PDQ], dof[kk], dp[kb]);
+        if (y + PDQ < NM1) fr[y % PDQ] = frag1(y + PDQ);
+        if (y % (NM1 / NPIECE) == 0) copy_piece(y / (NM1 / NPIECE), (t + 1) & 1, kpn, vpn, last_n);
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
+    // first K^T operands of the dQ^T product are requested now, so that they arrive during the dS arithmetic
+    constexpr int NM2 = 4 * (D / 32);
+    auto frag2 = [&](int y) -> bf16x8 {
+      const int kb = y / (2 * (D / 32)), cc = (y / (D / 32)) % 2, mb = y % (D / 32);
+      const uint16_t* krow = Kb + (32 * kb + 16 * cc) * D;
+      return join_tr(lds_read_tr4(krow + (kt_base0 ^ (mb << 5))), lds_read_tr4(krow + (kt_base1 ^ (mb << 5))));
+    };
+    bf16x8 f2[PDQ];
+#pragma unroll
+    for (int x = 0; x < PDQ; ++x) f2[x] = frag2(x);
+    __builtin_amdgcn_sched_barrier(0);
     const bool tail = (j + 1) * BKV > N;
     uint32_t dsk[2][8];
 #pragma unroll
@@ -228,20 +248,17 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(DqArgs a) {
         }
         dsk[kb][u] = pack_bf16(ds2[0], ds2[1]);
       }
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- dQ^T += K^T dS^T
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int cc = 0; cc < 2; ++cc) {
-        const u32x4 du = {dsk[kb][4 * cc], dsk[kb][4 * cc + 1], dsk[kb][4 * cc + 2], dsk[kb][4 * cc + 3]};
-        const bf16x8 dsb = __builtin_bit_cast(bf16x8, du);
-        const uint16_t* krow = Kb + (32 * kb + 16 * cc) * D;
-#pragma unroll
-        for (int mb = 0; mb < D / 32; ++mb) {
-          const bf16x8 kta = join_tr(lds_read_tr4(krow + kt_off[0][mb]), lds_read_tr4(krow + kt_off[1][mb]));
-          acc[mb] = mfma32(kta, dsb, acc[mb]);
-        }
-      }
-    if (more) store_tile((t + 1) & 1);
+    for (int y = 0; y < NM2; ++y) {
+      const int kb = y / (2 * (D / 32)), cc = (y / (D / 32)) % 2, mb = y % (D / 32);
+      const u32x4 du = {dsk[kb][4 * cc], dsk[kb][4 * cc + 1], dsk[kb][4 * cc + 2], dsk[kb][4 * cc + 3]};
+      acc[mb] = mfma32(f2[y % PDQ], __builtin_bit_cast(bf16x8, du), acc[mb]);
+      if (y + PDQ < NM2) f2[y % PDQ] = frag2(y + PDQ);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    raw_copies_done();    // the copies requested in this iteration have landed
     __syncthreads();
   }
 

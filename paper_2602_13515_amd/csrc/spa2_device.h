@@ -93,6 +93,26 @@ __device__ __forceinline__ float dot2_ones(uint32_t p, float acc) {
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Direct global -> LDS copy, 16 bytes per lane: lane l's bytes land at lds_dst + 16 l (lds_dst wave-uniform);
+// the source is a wave-uniform base plus a 32-bit byte offset per lane.  Issued as an assembly statement so
+// that the compiler's wait-count insertion does not see it: through the builtin, LDS reads that follow a copy
+// are made to wait for it (the two cannot be told apart by address).  The caller therefore owns the
+// ordering: raw_copies_done() before the barrier that publishes the tile.  In-order completion of vector
+// memory operations keeps the compiler's own counted waits safe (they can only wait for more, never less).
+__device__ __forceinline__ void raw_copy16_to_lds(const void* src_base, uint32_t src_off, const uint16_t* lds_dst) {
+#if defined(__HIP_DEVICE_COMPILE__)      // (the host pass of hipcc parses device functions too and knows no m0)
+  // (wave-uniform by contract; the lane read makes that visible to the register allocator)
+  const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)(lptr_t*)lds_dst);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :: "s"(lds_addr), "v"(src_off), "s"(src_base) : "memory", "m0");
+#endif
+}
+__device__ __forceinline__ void raw_copies_done() {
+#if defined(__HIP_DEVICE_COMPILE__)
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#endif
+}
+
 // XOR-swizzled LDS tile: rows of D bf16, unpadded; the 16-byte chunk c of row r lives at chunk position
 // c ^ swz<D>(r).  The function is chosen so that BOTH access patterns the kernels use are free of bank
 // conflicts (64 banks x 4 bytes): 16 lanes reading the same chunk of 16 consecutive rows (MFMA operand read
