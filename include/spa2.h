@@ -162,6 +162,21 @@ int spa2_bwd_dq(const void* q, const void* k, const void* v, const void* d_o, co
                 const spa2_shape* shape, const spa2_pattern* pattern, float scale,
                 void* dq, const void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- diagnostics: the error of sparse attention and its two parts (Sec. 3.1) ----
+ * For every query row, with tau = exp(lse_sparse - lse_dense) the attention mass the mask retains:
+ *   o_dense - o_sparse = (o_dense - tau * o_sparse)  +  (tau - 1) * o_sparse
+ *                         dropped error                  renormalisation error
+ * out, fp64 [B,H,5], per (batch, head) over all rows and channels:
+ *   [0] sum |o_dense - o_sparse|   [1] sum |o_dense|   (their ratio is the relative L1 error of Sec. 3.2)
+ *   [2] sum |o_dense - tau o_sparse|   [3] sum |(tau - 1) o_sparse|   [4] sum over rows of tau.
+ * o_sparse / lse_sparse come from spa2_fwd on the pattern under study, o_dense / lse_dense from spa2_fwd on the
+ * pattern spa2_pattern_full writes; the four token tensors share `shape` (bf16; lse fp32 [B,H,N]).  Device
+ * pointers, caller-owned; workspace of spa2_error_workspace_bytes(shape) bytes, 16-byte aligned (0 = bad shape).
+ * The reduction order is fixed: results are deterministic.  Errors as for spa2_fwd. */
+size_t spa2_error_workspace_bytes(const spa2_shape* shape);
+int spa2_error_terms(const void* o_sparse, const void* o_dense, const float* lse_sparse, const float* lse_dense,
+                     const spa2_shape* shape, double* out, void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

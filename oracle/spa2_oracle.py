@@ -343,6 +343,24 @@ def error_terms(p_row, m_row, v):
     return tau, o, o_s, dropped, renorm
 
 
+def error_sums(q, k, v, mbar, scale: float | None = None):
+    """Sec. 3.1 summed over one head: with the full attention weights P of every query row and the token-level
+    mask m expanded from the block mask, returns the L1 norms (over all rows and channels) of o - o_s, of o,
+    of the dropped error and of the renormalisation error, and the sum of tau over the rows.  Dense N x N
+    work: small inputs only."""
+    q = np.asarray(q, np.float64); k = np.asarray(k, np.float64); v = np.asarray(v, np.float64)
+    n, d = q.shape
+    scale = 1.0 / np.sqrt(d) if scale is None else scale
+    p = softmax_rows(q @ k.T * scale)
+    m = expand_mask(mbar, n).astype(np.float64)
+    tot = ref = drop = ren = tau_sum = 0.0
+    for r in range(n):
+        tau, o, o_s, dropped, renorm = error_terms(p[r], m[r], v)
+        tot += np.abs(o - o_s).sum(); ref += np.abs(o).sum()
+        drop += np.abs(dropped).sum(); ren += np.abs(renorm).sum(); tau_sum += tau
+    return tot, ref, drop, ren, tau_sum
+
+
 # --------------------------------------------------------------------------
 # Batched wrappers: [B, H, N, d] arrays, heads independent
 # --------------------------------------------------------------------------

@@ -84,6 +84,10 @@ def _load():
     lib.spa2_bwd_dkdv.argtypes = [vp, vp, vp, vp, vp, shp, pat, f32, vp, vp, vp, sz, vp]
     lib.spa2_bwd_dq.restype = ctypes.c_int
     lib.spa2_bwd_dq.argtypes = [vp, vp, vp, vp, vp, shp, pat, f32, vp, vp, sz, vp]
+    lib.spa2_error_workspace_bytes.restype = sz
+    lib.spa2_error_workspace_bytes.argtypes = [shp]
+    lib.spa2_error_terms.restype = ctypes.c_int
+    lib.spa2_error_terms.argtypes = [vp, vp, vp, vp, shp, vp, vp, sz, vp]
     _lib = lib
     return lib
 
@@ -91,7 +95,7 @@ def _load():
 EXPORTED_SYMBOLS = ("spa2_version", "spa2_strerror", "spa2_topk_blocks", "spa2_mask_workspace_bytes",
                     "spa2_bwd_workspace_bytes", "spa2_mask", "spa2_mask_pool", "spa2_mask_select",
                     "spa2_mask_columns", "spa2_pattern_full", "spa2_fwd", "spa2_bwd", "spa2_bwd_delta",
-                    "spa2_bwd_dkdv", "spa2_bwd_dq")
+                    "spa2_bwd_dkdv", "spa2_bwd_dq", "spa2_error_workspace_bytes", "spa2_error_terms")
 
 
 # ------------------------------------------------------------------ plumbing (memory only)
@@ -269,3 +273,20 @@ def spa2_bwd_dq(q, k, v, d_o, lse, pattern: Pattern, scale: float, dq, workspace
     _check(_load().spa2_bwd_dq(q.data_ptr(), k.data_ptr(), v.data_ptr(), d_o.data_ptr(), lse.data_ptr(),
                                ctypes.byref(shape), ctypes.byref(pat), float(scale), dq.data_ptr(),
                                workspace.data_ptr(), _nbytes(workspace), _stream(q)), "spa2_bwd_dq")
+
+
+# ------------------------------------------------------------------ diagnostics
+def spa2_error_workspace_bytes(o: torch.Tensor) -> int:
+    return int(_load().spa2_error_workspace_bytes(ctypes.byref(_shape_of(o))))
+
+
+def spa2_error_terms(o_sparse: torch.Tensor, o_dense: torch.Tensor, lse_sparse: torch.Tensor,
+                     lse_dense: torch.Tensor, out: torch.Tensor, workspace: torch.Tensor) -> None:
+    """out: float64 [B, H, 5] = sums of |o_dense - o_sparse|, |o_dense|, |dropped|, |renormalisation|, tau."""
+    _same_layout(o_sparse, o_dense)
+    if out.dtype != torch.float64 or not out.is_contiguous():
+        raise ValueError("out is a contiguous float64 [B, H, 5] tensor")
+    rc = _load().spa2_error_terms(o_sparse.data_ptr(), o_dense.data_ptr(), lse_sparse.data_ptr(),
+                                  lse_dense.data_ptr(), ctypes.byref(_shape_of(o_sparse)), out.data_ptr(),
+                                  workspace.data_ptr(), _nbytes(workspace), _stream(o_sparse))
+    _check(rc, "spa2_error_terms")

@@ -234,4 +234,21 @@ int spa2_bwd(const void* q, const void* k, const void* v, const void* o, const v
   return spa2_bwd_dq(q, k, v, d_o, lse, shape, pattern, scale, dq, workspace, workspace_bytes, stream);
 }
 
+
+size_t spa2_error_workspace_bytes(const spa2_shape* shape) {
+  if (check_shape(shape) != SPA2_OK) return 0;
+  return round256(error_ws_bytes(make_dims(*shape)));
+}
+
+int spa2_error_terms(const void* o_sparse, const void* o_dense, const float* lse_sparse, const float* lse_dense,
+                     const spa2_shape* shape, double* out, void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != SPA2_OK) return rc;
+  if (!o_sparse || !o_dense || !lse_sparse || !lse_dense || !out) return SPA2_ERR_NULL;
+  if (!aligned16(o_sparse) || !aligned16(o_dense) || !aligned16(workspace)) return SPA2_ERR_ALIGN;
+  const Dims m = make_dims(*shape);
+  if (!workspace || workspace_bytes < error_ws_bytes(m)) return SPA2_ERR_WORKSPACE;
+  return launch_error_terms(o_sparse, o_dense, lse_sparse, lse_dense, m, out, workspace, (hipStream_t)stream) == hipSuccess
+             ? SPA2_OK : SPA2_ERR_LAUNCH;
+}
 }  // extern "C"

@@ -43,4 +43,8 @@ hipError_t launch_bwd_dkdv(const void* q, const void* k, const void* v, const vo
                            const float* delta, const Dims& m, const int32_t* col_cnt, const int32_t* col_idx,
                            const int32_t* col_order, float scale, void* dk, void* dv, hipStream_t stream);
 
+size_t error_ws_bytes(const Dims& m);
+hipError_t launch_error_terms(const void* o_sparse, const void* o_dense, const float* lse_sparse,
+                              const float* lse_dense, const Dims& m, double* out, void* ws, hipStream_t stream);
+
 }  // namespace spa2

@@ -376,3 +376,24 @@ def test_q_blocks_subset_matches_full_evaluation():
     o_sub, lse_sub = orc.attention_gather(q, k, v, m, q_blocks=[2])
     o_all, lse_all = orc.attention_gather(q, k, v, m)
     np.testing.assert_array_equal(o_sub[256:384], o_all[256:384])
+
+
+# ------------------------------------------------------------------ Sec. 3.1 summed over a head
+def test_error_sums_identities():
+    """tau of a row equals exp(LSE_sparse - LSE_full); the two parts add up to the error row by row, so the
+    L1 norm of the total is at most the sum of the L1 norms of the parts; a full mask has no error."""
+    rng = np.random.default_rng(11)
+    n, d = 300, 16
+    q, k, v = rng.standard_normal((3, n, d))
+    mbar, _ = orc.block_mask(q, k, 1, 0.5)
+    tot, ref, drop, ren, tau_sum = orc.error_sums(q, k, v, mbar)
+    _, lse_s = orc.attention_gather(q, k, v, mbar)
+    _, lse_f = orc.attention_gather(q, k, v, np.ones_like(mbar))
+    assert abs(np.exp(lse_s - lse_f).sum() - tau_sum) < 1e-9
+    assert 0 < tot <= drop + ren + 1e-12 and ref > 0
+    # against the outputs themselves: o - o_s from the two attention calls
+    o_s, _ = orc.attention_gather(q, k, v, mbar)
+    o_f = orc.attention_definition(q, k, v, np.ones_like(mbar))[0]
+    assert abs(np.abs(o_f - o_s).sum() - tot) < 1e-9 * max(1.0, tot)
+    full = orc.error_sums(q, k, v, np.ones_like(mbar))
+    assert full[0] < 1e-12 and full[2] < 1e-12 and full[3] < 1e-12 and abs(full[4] - n) < 1e-9
