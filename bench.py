@@ -84,8 +84,8 @@ def cpu_baseline(w, q, k, v, do, head=(0, 0)):
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (the path shards by head with no "
-              "communication, see DESIGN.md)", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (the path would shard by head, with no "
+              "communication between the shards)", file=sys.stderr)
         sys.exit(2)
     import torch
     import paper_2602_13515_amd as spa2

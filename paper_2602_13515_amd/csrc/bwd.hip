@@ -553,7 +553,7 @@ __global__ __launch_bounds__(512, 2) void dkdv_kernel(DkvArgs a) {
     __syncthreads();      // also waits for the global -> LDS copies requested in this iteration
   }
 
-  // sum the partial results of the four query groups of each key half.  Round 1: dK, round 2: dV.
+  // sum the partial results of the four query groups of each key half: first pass dK, second pass dV.
   // Wave (wq, wk) finishes output block mb = wq (channels 32wq..32wq+31) of its key half.
   float* scratch = (float*)smem;
   constexpr int REGION = (D / 32) * 16 * 64;          // floats per wave
