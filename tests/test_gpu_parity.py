@@ -88,6 +88,8 @@ MASK_CASES = [
     ("stress-small", _small("st", 8192, 128, kind="stress", H=2, B=2), 0.05, 0.8),
     ("wide-row", _small("wide", 20000, 64, kind="lowrank", H=1), 0.03, 0.5),     # Tn = 313 -> 512-wide sort
     ("very-short", _small("vs", 100, 64, H=1), 0.5, 0.5),
+    ("longest-row", _small("max", 64 * 8192 - 30, 64, kind="lowrank", H=1), 0.01, 0.3),   # Tn = 8192, the widest row
+    ("everything", _small("all", 3000, 128, H=2), 1.0, 1.0),                              # k = 100 %: full mask
 ]
 
 
