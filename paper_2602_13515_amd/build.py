@@ -23,6 +23,8 @@ FLAGS = [
     # packed-fp32 VALU forms are kept off (the compiler must not fuse float pairs)
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
+    # raw_copy16_to_lds names m0 as clobbered (it is how the LDS address of a direct copy is passed)
+    "-Wno-inline-asm",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]
 

@@ -99,6 +99,8 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 // are made to wait for it (the two cannot be told apart by address).  The caller therefore owns the
 // ordering: raw_copies_done() before the barrier that publishes the tile.  In-order completion of vector
 // memory operations keeps the compiler's own counted waits safe (they can only wait for more, never less).
+// m0 carries the LDS address and is declared clobbered; a kernel that uses this helper must not also rely on
+// the compiler keeping a value of its own in m0 across it (the builtin form of the same copy would).
 __device__ __forceinline__ void raw_copy16_to_lds(const void* src_base, uint32_t src_off, const uint16_t* lds_dst) {
 #if defined(__HIP_DEVICE_COMPILE__)      // (the host pass of hipcc parses device functions too and knows no m0)
   // (wave-uniform by contract; the lane read makes that visible to the register allocator)
