@@ -123,7 +123,8 @@ __device__ __forceinline__ uint64_t fixed62(uint32_t fbits) {
   return sh >= 0 ? (m << sh) : (sh > -24 ? (m >> (-sh)) : 0);
 }
 
-// NP: padded row length (power of two >= T_n, >= 256).  R = 4 rows of one head per workgroup.
+// NP: padded row length (a multiple of 256 >= T_n; the closer, the fewer score columns are computed for
+// nothing).  R = 4 rows of one head per workgroup.
 //
 // Selection without sorting.  Entries are ordered by the 64-bit key (bits(Pbar) << 32) | ~j (larger Pbar
 // first, equal Pbar: lower block index first).  With cnt_gt(e) / mass_gt(e) the number / total Pbar of
@@ -135,11 +136,17 @@ __device__ __forceinline__ uint64_t fixed62(uint32_t fbits) {
 // that break ties): per pass a 256-bin histogram of count and mass of the entries that match the prefix
 // found so far, then one wave per row walks the bins from the top and picks the lowest bin whose top
 // entry is still selected.
+constexpr int score_group(int jj) {
+  for (int g = 8; g > 1; --g)
+    if (jj % g == 0) return g;
+  return 1;
+}
+
 template <int NP, int R>
 __global__ __launch_bounds__(256) void select_kernel(SelArgs a) {
   static_assert(R == 4, "one wave scans the histogram of one row");
   constexpr int JJ = NP / 256;            // score columns per thread per row
-  constexpr int G = JJ < 8 ? JJ : 8;      // columns per thread processed together in the score loop
+  constexpr int G = score_group(JJ);      // columns per thread processed together in the score loop (divides JJ)
   constexpr int E = R * NP / 256;         // consecutive block indices per thread in the compaction pass
   constexpr int SEG_T = 256 / R;          // threads per row in the compaction pass
   __shared__ uint32_t h_cnt[R][256];
@@ -367,12 +374,14 @@ hipError_t launch_select(const float* qbar, const float* kbar, const Dims& m, in
   a.d = m.d; a.Tm = m.Tm; a.Tn = m.Tn; a.TnP = m.Tn; a.groups = 0;
   a.k_cnt = topk_blocks; a.top_p = top_p; a.scale = scale;
   const int BH = m.B * m.H;
-  if (m.Tn <= 256)       launch_select_t<256, 4>(a, BH, stream);
-  else if (m.Tn <= 512)  launch_select_t<512, 4>(a, BH, stream);
-  else if (m.Tn <= 1024) launch_select_t<1024, 4>(a, BH, stream);
-  else if (m.Tn <= 2048) launch_select_t<2048, 4>(a, BH, stream);
-  else if (m.Tn <= 4096) launch_select_t<4096, 4>(a, BH, stream);
-  else                   launch_select_t<8192, 4>(a, BH, stream);
+  // the smallest instantiated width that holds the row: steps of 256 up to 2048, then of 512, then of 1024
+#define SPA2_SELECT_CASE(np) if (m.Tn <= np) { launch_select_t<np, 4>(a, BH, stream); return hipGetLastError(); }
+  SPA2_SELECT_CASE(256)  SPA2_SELECT_CASE(512)  SPA2_SELECT_CASE(768)  SPA2_SELECT_CASE(1024)
+  SPA2_SELECT_CASE(1280) SPA2_SELECT_CASE(1536) SPA2_SELECT_CASE(1792) SPA2_SELECT_CASE(2048)
+  SPA2_SELECT_CASE(2560) SPA2_SELECT_CASE(3072) SPA2_SELECT_CASE(3584) SPA2_SELECT_CASE(4096)
+  SPA2_SELECT_CASE(5120) SPA2_SELECT_CASE(6144) SPA2_SELECT_CASE(7168)
+#undef SPA2_SELECT_CASE
+  launch_select_t<8192, 4>(a, BH, stream);
   return hipGetLastError();
 }
 
