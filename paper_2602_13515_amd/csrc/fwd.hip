@@ -137,10 +137,10 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdArgs a) {
   const int s16 = lane & 15, blk16 = lane >> 4;
   const int v_off = (4 * hf + (s16 >> 2)) * C::VP + 16 * (blk16 & 1) + 4 * (s16 & 3);  // V transposing read
 
-  // Pipeline: tile T is requested at the start of iteration T-3 into the staging set of its parity,
-  // written to LDS buffer T&1 at the start of iteration T-1 (that buffer held tile T-2, fully consumed
-  // before the barrier that ended iteration T-2), and consumed in iteration T.  Two tiles are in flight
-  // at any time and one barrier per tile is enough.
+  // Pipeline: tile T is requested during iteration T-3 into the staging set of its parity, written to
+  // LDS buffer T&1 during iteration T-1 (that buffer held tile T-2, fully consumed before the barrier that
+  // ended iteration T-2), and consumed in iteration T.  Two tiles are in flight at any time and one
+  // barrier per tile is enough.
   // The list of selected key blocks is read with scalar loads, one entry per iteration and one iteration
   // ahead of its use: jw[m] is the (clamped) block of tile t+m, jpre the entry that becomes jw[3] next.
   auto list_at = [&](int t) -> int { return min(max(idx[min(t, cnt - 1)], 0), a.Tn - 1); };
