@@ -386,17 +386,31 @@ hipError_t launch_select(const float* qbar, const float* kbar, const Dims& m, in
 }
 
 // ------------------------------------------------------------------ column lists
+// One workgroup lists 64 key blocks of one head: thread (seg, c) walks a quarter of the query blocks of
+// column c twice, first counting, then (after the four counts of the column have been exchanged through
+// LDS) writing its ascending piece of the list at the right offset.
 __global__ __launch_bounds__(256) void columns_kernel(const uint8_t* mask, int Tm, int Tn, int32_t* col_cnt,
                                                       int32_t* col_idx) {
+  __shared__ int seg_cnt[4][64];
   const int bh = blockIdx.y;
-  const int j = blockIdx.x * 256 + threadIdx.x;
-  if (j >= Tn) return;
-  const uint8_t* mp = mask + (int64_t)bh * Tm * Tn + j;
+  const int c = threadIdx.x & 63, seg = threadIdx.x >> 6;
+  const int j = blockIdx.x * 64 + c;
+  const int per = (Tm + 3) / 4;
+  const int i0 = seg * per, i1 = min(Tm, i0 + per);
+  const bool live = j < Tn;
+  const uint8_t* mp = mask + (int64_t)bh * Tm * Tn + (live ? j : 0);
+  int n = 0;
+  if (live)
+    for (int i = i0; i < i1; ++i) n += mp[(int64_t)i * Tn] != 0;
+  seg_cnt[seg][c] = n;
+  __syncthreads();
+  if (!live) return;
+  int at = 0;
+  for (int s2 = 0; s2 < seg; ++s2) at += seg_cnt[s2][c];
   int32_t* out = col_idx + ((int64_t)bh * Tn + j) * Tm;
-  int c = 0;
-  for (int i = 0; i < Tm; ++i)
-    if (mp[(int64_t)i * Tn]) out[c++] = i;
-  col_cnt[(int64_t)bh * Tn + j] = c;
+  for (int i = i0; i < i1; ++i)
+    if (mp[(int64_t)i * Tn]) out[at++] = i;
+  if (seg == 3) col_cnt[(int64_t)bh * Tn + j] = at;
 }
 
 // Launch order of the key blocks of one head for the dK/dV kernel: longest column first, dealt round-robin
@@ -433,7 +447,7 @@ __global__ __launch_bounds__(256) void col_order_kernel(const int32_t* col_cnt, 
 
 hipError_t launch_columns(const uint8_t* mask, const Dims& m, int32_t* col_cnt, int32_t* col_idx,
                           int32_t* col_order, hipStream_t stream) {
-  const dim3 grid((unsigned)((m.Tn + 255) / 256), (unsigned)(m.B * m.H)), block(256);
+  const dim3 grid((unsigned)((m.Tn + 63) / 64), (unsigned)(m.B * m.H)), block(256);
   hipLaunchKernelGGL(columns_kernel, grid, block, 0, stream, mask, m.Tm, m.Tn, col_cnt, col_idx);
   if (col_order) {
     const dim3 g2((unsigned)(m.B * m.H));
