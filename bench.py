@@ -55,9 +55,9 @@ def tile_flops_per_d(mask, N):
     return float((per_row * rv).sum().item())
 
 
-def cpu_baseline(w, q, k, v, do, head=(0, 0)):
-    """The fp64 oracle, as it stands, on one head of the same workload: pooling, pooled map,
-    selection, gather-form attention forward and gradients."""
+def cpu_baseline(w, q, k, v, do, heads=((0, 0), (0, -1))):
+    """The fp64 oracle, as it stands, on two heads of the same workload (the first and the last): pooling,
+    pooled map, selection, gather-form attention forward and gradients."""
     import numpy as np
     from oracle import spa2_oracle as orc
     try:
@@ -65,20 +65,23 @@ def cpu_baseline(w, q, k, v, do, head=(0, 0)):
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         threads = os.cpu_count() or 1
-    b, h = head
-    qd, kd, vd, dod = (t[b, h].to("cpu").double().numpy() for t in (q, k, v, do))
-    t0 = time.perf_counter()
-    k_cnt = orc.topk_blocks(w.k_frac, w.Tn)
-    m, _ = orc.block_mask(qd, kd, k_cnt, float(np.float32(w.top_p)))
-    orc.attention_bwd_gather(qd, kd, vd, m, dod)
-    dt = time.perf_counter() - t0
-    Tm, Tn = m.shape
-    rv = np.full(Tm, 128.0); rv[-1] = w.N - 128 * (Tm - 1)
-    cv = np.full(Tn, 64.0); cv[-1] = w.N - 64 * (Tn - 1)
-    flops = float((m * rv[:, None] * cv[None, :]).sum()) * 14.0 * w.d
+    heads = sorted({(b % w.B, h % w.H) for b, h in heads})
+    flops, tiles, dt = 0.0, 0, 0.0
+    for b, h in heads:
+        qd, kd, vd, dod = (t[b, h].to("cpu").double().numpy() for t in (q, k, v, do))
+        t0 = time.perf_counter()
+        k_cnt = orc.topk_blocks(w.k_frac, w.Tn)
+        m, _ = orc.block_mask(qd, kd, k_cnt, float(np.float32(w.top_p)))
+        orc.attention_bwd_gather(qd, kd, vd, m, dod)
+        dt += time.perf_counter() - t0
+        Tm, Tn = m.shape
+        rv = np.full(Tm, 128.0); rv[-1] = w.N - 128 * (Tm - 1)
+        cv = np.full(Tn, 64.0); cv[-1] = w.N - 64 * (Tn - 1)
+        flops += float((m * rv[:, None] * cv[None, :]).sum()) * 14.0 * w.d
+        tiles += int(m.sum())
     return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"1 of {w.B * w.H} heads (b={b}, h={h}) of {w.name}: mask + fwd + bwd in fp64 numpy, "
-                      f"{dt:.1f} s, {int(m.sum())} tiles"}
+            "sample": f"{len(heads)} of {w.B * w.H} heads {heads} of {w.name}: mask + fwd + bwd in fp64 numpy, "
+                      f"{dt:.1f} s, {tiles} tiles"}
 
 
 def main():
