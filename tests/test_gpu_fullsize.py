@@ -110,6 +110,24 @@ def test_wan_like_layers_sampled(w):
         _check_head_samples(w, b, h, q, k, v, do, pat, o, lse, dq, dk, dv, q_blocks, kv_blocks)
 
 
+def test_head_dim_64_layer_sampled():
+    """The d = 64 instantiations of every kernel on a layer long enough for many tiles per row and column,
+    batch 2, with a ragged tail (20,010 = 156 * 128 + 42 = 312 * 64 + 42)."""
+    w = wl.Workload("d64-20k", 2, 3, 20010, 64, 0.05, 0.8, "lowrank", True)
+    print(f"workload {w.name}: B={w.B} H={w.H} N={w.N} d={w.d}", flush=True)
+    q, k, v, do = wl.make_inputs(w, seed=0, device=dev())
+    k_cnt, pat, pbar, o, lse, dq, dk, dv = _run_path(w, q, k, v, do)
+    _properties(w, pat, o, lse, dq, dk, dv, k_cnt)
+    b, h = 1, 2
+    ref_pbar = orc.pooled_map(f64(q[b, h]), f64(k[b, h]))
+    r = mask_protocol(pat.mask[b, h].cpu().numpy(), pbar[b, h].cpu().numpy(), ref_pbar, k_cnt, w.top_p)
+    print(f"  head ({b},{h}) mask protocol: {r}", flush=True)
+    assert r["stage1_max_rel"] <= 1e-5 and r["stage2_unexplained"] == 0 and r["stage3_unexplained"] == 0
+    rc = pat.row_cnt[b, h].cpu().numpy(); cc = pat.col_cnt[b, h].cpu().numpy()
+    _check_head_samples(w, b, h, q, k, v, do, pat, o, lse, dq, dk, dv,
+                        q_blocks=sorted({0, int(rc.argmax()), w.Tm - 1}), kv_blocks=sorted({int(cc.argmax()), w.Tn - 1}))
+
+
 STRESS_SETTINGS = [(kf, p) for kf in (0.02, 0.05, 0.10) for p in (0.5, 0.8, 0.95)]
 
 
