@@ -232,7 +232,7 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdArgs a) {
     for (int v = 1; v < 16; ++v) mx = fmaxf(mx, s[0][v]);
 #pragma unroll
     for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[1][v]);
-    mx = fmaxf(mx, other_half(mx));
+    mx = max_halves(mx);
     const float m_new = fmaxf(m_run, mx * a.scale_log2);
     // rescale the accumulators (steps 13-14) only when some row's maximum moved: after the first
     // few tiles it rarely does, and the branch is uniform over the wave
@@ -276,7 +276,7 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdArgs a) {
   }
 
   // O_i = diag(l)^-1 O (step 18) and the log-sum-exp the backward pass needs
-  const float l_tot = l_run + other_half(l_run);
+  const float l_tot = sum_halves(l_run);
   const float inv = 1.f / l_tot;
   if (qrow < N) {
     uint16_t* op = a.o + base + (int64_t)qrow * a.sn + 4 * hf;

@@ -23,16 +23,11 @@ constexpr int BKV = 64;
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 
-// Operand layouts of the two bf16 MFMA shapes used here (lane l of a wave64):
+// Operand layout of the bf16 MFMA shape used here (lane l of a wave64):
 //   32x32x16:  A[m][k]: m = l%32, k = 8*(l/32)+s (s=0..7)   B[k][n]: n = l%32, same k
 //              C[m][n]: n = l%32, m = 8*(v/4) + 4*(l/32) + v%4 for accumulator register v = 0..15
-//   16x16x32:  A[m][k]: m = l%16, k = 8*(l/16)+s            B[k][n]: n = l%16, same k
-//              C[m][n]: n = l%16, m = 4*(l/16) + v for v = 0..3
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
-}
-__device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
-  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
 
 // Two floats -> packed bf16 pair (round to nearest even), low half = a.
@@ -40,12 +35,6 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   f32x2 v = {a, b};
   bf16x2 r = __builtin_convertvector(v, bf16x2);
   return __builtin_bit_cast(uint32_t, r);
-}
-
-__device__ __forceinline__ bf16x8 make_bf16x8(float x0, float x1, float x2, float x3,
-                                              float x4, float x5, float x6, float x7) {
-  u32x4 u = {pack_bf16(x0, x1), pack_bf16(x2, x3), pack_bf16(x4, x5), pack_bf16(x6, x7)};
-  return __builtin_bit_cast(bf16x8, u);
 }
 
 __device__ __forceinline__ float bf16_to_float(uint16_t x) {
@@ -69,13 +58,8 @@ __device__ __forceinline__ bf16x8 join_tr(u32x2 lo, u32x2 hi) {
   return __builtin_bit_cast(bf16x8, u);
 }
 
-// Exchange between the two 32-lane halves of a wave: returns, in every lane,
-// the value held by the lane 32 positions away.
-__device__ __forceinline__ float other_half(float x) {
-  return __shfl_xor(x, 32, 64);
-}
-// The same exchange on the vector ALU (v_permlane32_swap), without a trip through LDS: returns max / sum of
-// the values that lanes l and l^32 hold, in both lanes.
+// Exchange between the two 32-lane halves of a wave on the vector ALU (v_permlane32_swap), without a trip
+// through LDS: max / sum of the values that lanes l and l^32 hold, in both lanes.
 __device__ __forceinline__ void both_halves(float x, float& lo, float& hi) {
   const uint32_t u = __builtin_bit_cast(uint32_t, x);
   const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
