@@ -37,10 +37,6 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   return __builtin_bit_cast(uint32_t, r);
 }
 
-__device__ __forceinline__ float bf16_to_float(uint16_t x) {
-  return __builtin_bit_cast(float, (uint32_t)x << 16);
-}
-
 // Transposing LDS read (ds_read_b64_tr_b16).  Within each group of 16 lanes,
 // lane s supplies the address of four consecutive 16-bit elements; lane i of
 // the group receives element (i%4) of the data addressed by lanes i/4, 4+i/4,
