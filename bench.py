@@ -72,15 +72,18 @@ def cpu_baseline(w, q, k, v, do, heads=((0, 0), (0, -1))):
         t0 = time.perf_counter()
         k_cnt = orc.topk_blocks(w.k_frac, w.Tn)
         m, _ = orc.block_mask(qd, kd, k_cnt, float(np.float32(w.top_p)))
-        orc.attention_bwd_gather(qd, kd, vd, m, dod)
+        if w.backward:
+            orc.attention_bwd_gather(qd, kd, vd, m, dod)
+        else:
+            orc.attention_gather(qd, kd, vd, m)
         dt += time.perf_counter() - t0
         Tm, Tn = m.shape
         rv = np.full(Tm, 128.0); rv[-1] = w.N - 128 * (Tm - 1)
         cv = np.full(Tn, 64.0); cv[-1] = w.N - 64 * (Tn - 1)
-        flops += float((m * rv[:, None] * cv[None, :]).sum()) * 14.0 * w.d
+        flops += float((m * rv[:, None] * cv[None, :]).sum()) * (14.0 if w.backward else 4.0) * w.d
         tiles += int(m.sum())
     return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"{len(heads)} of {w.B * w.H} heads {heads} of {w.name}: mask + fwd + bwd in fp64 numpy, "
+            "sample": f"{len(heads)} of {w.B * w.H} heads {heads} of {w.name}: mask + fwd{' + bwd' if w.backward else ''} in fp64 numpy, "
                       f"{dt:.1f} s, {tiles} tiles"}
 
 
@@ -119,9 +122,12 @@ def main():
         spa2.spa2_mask_select(q, k_cnt, w.top_p, scale, p, None, ws_m); mark(2)
         spa2.spa2_mask_columns(q, p); mark(3)
         spa2.spa2_fwd(q, k, v, p, scale, o, lse, o_res); mark(4)
-        spa2.spa2_bwd_delta(o, do, ws_b, o_res); mark(5)
-        spa2.spa2_bwd_dkdv(q, k, v, do, lse, p, scale, dk, dv, ws_b); mark(6)
-        spa2.spa2_bwd_dq(q, k, v, do, lse, p, scale, dq, ws_b); mark(7)
+        if w.backward:        # a forward-only configuration stops here (its stage times below read 0)
+            spa2.spa2_bwd_delta(o, do, ws_b, o_res); mark(5)
+            spa2.spa2_bwd_dkdv(q, k, v, do, lse, p, scale, dk, dv, ws_b); mark(6)
+            spa2.spa2_bwd_dq(q, k, v, do, lse, p, scale, dq, ws_b); mark(7)
+        else:
+            mark(5); mark(6); mark(7)
 
     if args.calibration_copy_mib > 0:
         src = torch.empty(args.calibration_copy_mib << 20, dtype=torch.uint8, device=dev).random_(0, 255)
@@ -146,7 +152,7 @@ def main():
     n_tiles = int(pat.mask.sum().item())
     density = n_tiles / pat.mask.numel()
     fwd_flops = 4.0 * units * w.d
-    bwd_flops = 10.0 * units * w.d
+    bwd_flops = 10.0 * units * w.d if w.backward else 0.0
     value = (fwd_flops + bwd_flops) / (ms_per_step * 1e-3) / 1e12
 
     # per-kernel rates.  Algorithmic FLOPs: fwd 4*r*c*d; backward 10*r*c*d of which the dK/dV kernel
@@ -154,17 +160,19 @@ def main():
     kern = {
         "spa2_fwd": {"ms": stage_ms["fwd"], "alg_tflops": fwd_flops / stage_ms["fwd"] / 1e9,
                      "executed_tflops": fwd_flops / stage_ms["fwd"] / 1e9},
-        "spa2_bwd_dkdv": {"ms": stage_ms["dkdv"], "alg_tflops": 8.0 * units * w.d / stage_ms["dkdv"] / 1e9,
-                          "executed_tflops": 8.0 * units * w.d / stage_ms["dkdv"] / 1e9},
-        "spa2_bwd_dq": {"ms": stage_ms["dq"], "alg_tflops": 2.0 * units * w.d / stage_ms["dq"] / 1e9,
-                        "executed_tflops": 6.0 * units * w.d / stage_ms["dq"] / 1e9},
     }
+    if w.backward:
+        kern["spa2_bwd_dkdv"] = {"ms": stage_ms["dkdv"], "alg_tflops": 8.0 * units * w.d / stage_ms["dkdv"] / 1e9,
+                                 "executed_tflops": 8.0 * units * w.d / stage_ms["dkdv"] / 1e9}
+        kern["spa2_bwd_dq"] = {"ms": stage_ms["dq"], "alg_tflops": 2.0 * units * w.d / stage_ms["dq"] / 1e9,
+                               "executed_tflops": 6.0 * units * w.d / stage_ms["dq"] / 1e9}
     pool_bytes = 2.0 * w.B * w.H * w.N * w.d * 2
     delta_bytes = 3.0 * w.B * w.H * w.N * w.d * 2 + 4.0 * w.B * w.H * w.N      # O, O residual, dO; D
     hbm = {
         "spa2_mask_pool": {"ms": stage_ms["pool"], "alg_gbs": pool_bytes / stage_ms["pool"] / 1e6},
-        "spa2_bwd_delta": {"ms": stage_ms["delta"], "alg_gbs": delta_bytes / stage_ms["delta"] / 1e6},
     }
+    if w.backward:
+        hbm["spa2_bwd_delta"] = {"ms": stage_ms["delta"], "alg_gbs": delta_bytes / stage_ms["delta"] / 1e6}
     dom = max(kern, key=lambda n: kern[n]["ms"])
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
@@ -185,7 +193,8 @@ def main():
 
         def dense_step():
             spa2.spa2_fwd(q, k, v, full, scale, o, lse, o_res)
-            spa2.spa2_bwd(q, k, v, o, do, lse, full, scale, dq, dk, dv, ws_b, o_res)
+            if w.backward:
+                spa2.spa2_bwd(q, k, v, o, do, lse, full, scale, dq, dk, dv, ws_b, o_res)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         e0.record()
@@ -194,7 +203,7 @@ def main():
         e1.record()
         torch.cuda.synchronize()
         dense_ms = e0.elapsed_time(e1) / args.dense_steps
-        dense_flops = 14.0 * float(w.B * w.H) * float(w.N) * float(w.N) * w.d
+        dense_flops = (14.0 if w.backward else 4.0) * float(w.B * w.H) * float(w.N) * float(w.N) * w.d
         dense = {"ms": dense_ms, "tflops": dense_flops / dense_ms / 1e9,
                  "speedup_attention_only": dense_ms / (stage_ms["fwd"] + stage_ms["delta"] + stage_ms["dkdv"] + stage_ms["dq"]),
                  "speedup_with_masker": dense_ms / ms_per_step}
@@ -212,7 +221,7 @@ def main():
         "mask_ms": stage_ms["pool"] + stage_ms["select"] + stage_ms["columns"],
         "fwd_ms": stage_ms["fwd"], "bwd_ms": stage_ms["delta"] + stage_ms["dkdv"] + stage_ms["dq"],
         "fwd_tflops": kern["spa2_fwd"]["alg_tflops"],
-        "bwd_tflops": bwd_flops / (stage_ms["delta"] + stage_ms["dkdv"] + stage_ms["dq"]) / 1e9,
+        "bwd_tflops": (bwd_flops / (stage_ms["delta"] + stage_ms["dkdv"] + stage_ms["dq"]) / 1e9) if w.backward else None,
         "dense": dense,
         "roofline": roofline, "kernels": kern, "hbm_kernels": hbm,
     }
