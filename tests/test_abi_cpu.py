@@ -164,3 +164,20 @@ def test_operator_has_no_cpu_path():
         spa2.sparge_attn2(x, x, x, 0.1, 0.5)
     with pytest.raises(ValueError):
         spa2.sparge_attn2(x.float(), x.float(), x.float(), 0.1, 0.5)
+
+
+def test_header_is_plain_c():
+    """The boundary is a C ABI: the header must compile as C99 without a HIP or C++ toolchain."""
+    import shutil
+    import subprocess
+    import tempfile
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    with tempfile.TemporaryDirectory() as td:
+        src = os.path.join(td, "t.c")
+        with open(src, "w") as f:
+            f.write('#include "spa2.h"\nint main(void) { spa2_shape s; spa2_pattern p; (void)s; (void)p; return SPA2_OK; }\n')
+        r = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only",
+                            "-I", os.path.join(ROOT, "include"), src], capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
