@@ -143,9 +143,28 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdArgs a) {
   // barrier per tile is enough.
   // The list of selected key blocks is read with scalar loads, one entry per iteration and one iteration
   // ahead of its use: jw[m] is the (clamped) block of tile t+m, jpre the entry that becomes jw[3] next.
-  auto list_at = [&](int t) -> int { return min(max(idx[min(t, cnt - 1)], 0), a.Tn - 1); };
+  // Where in its list a row starts is a free choice (the online softmax does not depend on the order of the
+  // tiles, up to rounding), and it is used to keep the rows that run on one XCD at the same time close
+  // together in key space: query block i starts at the first selected block at or after (i mod 64) / 64 of
+  // the key range and wraps around.  An XCD takes consecutive query blocks, and its workgroups start as slots
+  // free up, one row-duration spread over its 64 slots; so a row that starts 1/64 of a row-duration later
+  // also starts 1/64 of the key range further on: all of them sweep the keys together and share K/V tiles
+  // through the XCD's L2.  The start depends on the row alone, so results do not depend on the launch order.
+  int t0 = 0;
+  {
+    const int start_blk = (int)(((int64_t)(i & 63) * a.Tn) >> 6);
+    for (int c = 0; c < cnt; c += 64) {
+      const int e = c + lane;
+      const bool below = e < cnt && idx[min(e, cnt - 1)] < start_blk;
+      t0 += __builtin_popcountll(__builtin_amdgcn_ballot_w64(below));
+    }
+    t0 = __builtin_amdgcn_readfirstlane(t0);
+    if (t0 >= cnt) t0 = 0;
+  }
+  auto rot = [&](int t) -> int { const int p = min(t, cnt - 1) + t0; return p >= cnt ? p - cnt : p; };
+  auto list_at = [&](int t) -> int { return min(max(idx[rot(t)], 0), a.Tn - 1); };
   int jw[4] = {list_at(0), list_at(1), list_at(2), list_at(3)};
-  int jpre = idx[min(4, cnt - 1)];      // raw: clamped when it is used, so that nothing waits for it here
+  int jpre = idx[rot(4)];      // raw: clamped when it is used, so that nothing waits for it here
   // One piece of the staging work of an iteration: chunk r of K (p even) or V (p odd) of `next` goes to LDS
   // buffer `buf` (tile t+1, requested two iterations ago), then the same registers request tile t+3.  The
   // pieces are handed out between the MFMAs of the S^T loop: issued back to back, the eight requests would
@@ -177,7 +196,7 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdArgs a) {
     const char* vp3 = (const char*)a.v + tile3;
     const int last3 = min(BKV - 1, N - 1 - j3 * BKV);
     jw[0] = jw[1]; jw[1] = jw[2]; jw[2] = jw[3]; jw[3] = min(max(jpre, 0), a.Tn - 1);
-    jpre = idx[min(t + 5, cnt - 1)];
+    jpre = idx[rot(t + 5)];
     const uint16_t* Kb = Ks + (t & 1) * C::K_ELEMS;
     const uint16_t* Vb = Vs + (t & 1) * C::V_ELEMS;
 
