@@ -251,3 +251,45 @@ def test_error_codes_leave_outputs_untouched():
     assert e.value.code == -3                                      # d = 32 unsupported
     torch.cuda.synchronize()
     assert (pat.mask == 9).all()
+
+
+def test_whole_step_replays_from_a_hip_graph():
+    """The library allocates nothing and never synchronises, so mask -> fwd -> bwd can be captured once and
+    replayed; every replay (with eager work and synchronisations in between) must reproduce the eager result
+    bit for bit."""
+    w = _small("graph", 3000, 128, kind="lowrank", H=2, k=0.1, p=0.6)
+    q, k, v, do = (t.to(dev()) for t in wl.make_inputs(w, seed=7))
+    scale = 1.0 / math.sqrt(w.d)
+    k_cnt = spa2.spa2_topk_blocks(w.k_frac, w.Tn)
+    pat = spa2.alloc_pattern(w.B, w.H, w.N, dev())
+    ws_m = torch.empty(spa2.spa2_mask_workspace_bytes(q), dtype=torch.uint8, device=dev())
+    ws_b = torch.empty(spa2.spa2_bwd_workspace_bytes(q), dtype=torch.uint8, device=dev())
+    o = torch.empty_like(q); o_res = torch.empty_like(q)
+    lse = torch.empty((w.B, w.H, w.N), dtype=torch.float32, device=dev())
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
+
+    def step():
+        spa2.spa2_mask(q, k, k_cnt, w.top_p, scale, pat, None, ws_m)
+        spa2.spa2_fwd(q, k, v, pat, scale, o, lse, o_res)
+        spa2.spa2_bwd(q, k, v, o, do, lse, pat, scale, dq, dk, dv, ws_b, o_res)
+
+    step()
+    torch.cuda.synchronize()
+    eager = [t.clone() for t in (pat.mask, o, lse, dq, dk, dv)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        step()                                   # warm-up on the capture stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for t in (pat.mask, o, lse, dq, dk, dv):
+            t.zero_()                            # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for name, got, ref in zip(("mask", "O", "LSE", "dQ", "dK", "dV"), (pat.mask, o, lse, dq, dk, dv), eager):
+            assert torch.equal(got, ref), (rep, name)
