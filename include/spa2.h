@@ -28,8 +28,9 @@
  *   - Token tensors (Q, K, V, O, dO, dQ, dK, dV) share one layout given by
  *     spa2_shape: element (b, h, n, c) lives at b*sb + h*sh + n*sn + c, the
  *     head dimension is contiguous, base pointers are 16-byte aligned and
- *     sb, sh, sn are multiples of 8 elements.  [B,H,N,d] and [B,N,H,d] both
- *     fit.  Per-row vectors (LSE) and the pattern arrays are contiguous.
+ *     sb, sh, sn are multiples of 8 elements and sn is at most
+ *     SPA2_MAX_TOKEN_STRIDE.  [B,H,N,d] and [B,N,H,d] both fit.  Per-row
+ *     vectors (LSE) and the pattern arrays are contiguous.
  */
 #ifndef SPA2_H
 #define SPA2_H
@@ -45,6 +46,9 @@ extern "C" {
 #define SPA2_BKV 64
 /* longest row of key blocks the masker sorts in one workgroup (N <= 524288) */
 #define SPA2_MAX_TN 8192
+/* largest token stride in elements: the kernels reach the 128 rows of a tile
+ * with a 32-bit byte offset from the tile's base address */
+#define SPA2_MAX_TOKEN_STRIDE (1 << 23)
 
 enum {
   SPA2_OK = 0,

@@ -18,6 +18,8 @@ int check_shape(const spa2_shape* s) {
   if (s->d != 64 && s->d != 128) return SPA2_ERR_UNSUPPORTED;
   if (s->sb <= 0 || s->sh <= 0 || s->sn < s->d) return SPA2_ERR_SHAPE;
   if ((s->sb % 8) || (s->sh % 8) || (s->sn % 8)) return SPA2_ERR_ALIGN;
+  // the kernels address a tile as a 64-bit base plus a 32-bit byte offset of up to 128 token rows
+  if (s->sn > SPA2_MAX_TOKEN_STRIDE) return SPA2_ERR_SHAPE;
   if ((int64_t)s->B * s->H > (int64_t)1 << 24) return SPA2_ERR_SHAPE;
   return SPA2_OK;
 }

@@ -73,6 +73,8 @@ def test_argument_validation_happens_on_the_host():
     assert f(fake, fake, fake, ctypes.byref(_shape(bq=64)), ctypes.byref(full), 0.1, fake, None, fake, None) == -3
     assert f(fake, fake, fake, ctypes.byref(_shape(N=0)), ctypes.byref(full), 0.1, fake, None, fake, None) == -2
     assert f(fake, fake, fake, ctypes.byref(_shape(sn=132)), ctypes.byref(full), 0.1, fake, None, fake, None) == -4
+    wide = _shape(sn=(1 << 23) + 8, sh=1 << 40, sb=1 << 41)       # a tile's rows would not fit a 32-bit offset
+    assert f(fake, fake, fake, ctypes.byref(wide), ctypes.byref(full), 0.1, fake, None, fake, None) == -2
     m = lib.spa2_mask
     big = 1 << 30
     assert m(fake, fake, ctypes.byref(ok), 1, 0.5, 0.1, ctypes.byref(full), None, None, big, None) == -6
