@@ -142,6 +142,7 @@ def test_p_zero_is_plain_topk_and_k_zero_is_nucleus():
     for i in range(5):
         top = set(np.argsort(-pbar[i], kind="stable")[:7].tolist())     # library top-k
         assert set(np.flatnonzero(m[i]).tolist()) == top
+    assert (orc.prefix_lengths(pbar, 7, 0.0)[1] == 0).all()             # p = 0: the Top-p prefix is empty
     m = orc.hybrid_mask(pbar, 0, 0.7)
     for i in range(5):
         srt = np.sort(pbar[i])[::-1]
@@ -185,10 +186,17 @@ def test_pbar_rank_one_closed_form_against_library_softmax():
     q = np.zeros((3 * 128, d)); k = np.zeros((6 * 64, d))
     q[:, 0] = np.repeat(a, 128); k[:, 0] = np.repeat(b, 64)
     k[:, 1] = 7.0                                 # orthogonal to q: must not matter
+    # zero-mean offsets inside each block: +-0.5 on the two halves of a 128-token query block and of a 64-token
+    # key block.  They cancel only if Q is averaged over 128 tokens and K over 64.
+    q[:, 0] += np.tile(np.repeat([0.5, -0.5], 64), 3)
+    k[:, 0] += np.tile(np.repeat([0.5, -0.5], 32), 6)
     n = 384
     pbar = orc.pooled_map(q[:n], k[:n])
     expect = scipy_softmax(np.outer(a, b) / math.sqrt(d), axis=1)
     np.testing.assert_allclose(pbar, expect, rtol=1e-14)
+    # logits far beyond exp's range: the row softmax still matches the library's
+    big = np.array([[1000.0, 999.0, -1000.0], [-800.0, -801.0, -802.0]])
+    np.testing.assert_allclose(orc.softmax_rows(big), scipy_softmax(big, axis=1), rtol=1e-14)
     # transposing the roles of Q and K would give a 6x3 map / different numbers
     assert pbar.shape == (3, 6)
 
@@ -344,15 +352,21 @@ def test_gradient_closed_forms():
 
 def test_batched_wrappers_are_per_head():
     rng = np.random.default_rng(15)
-    q, k, v, do = (rng.normal(size=(1, 2, 256, 8)) for _ in range(4))
+    q, k, v, do = (rng.normal(size=(2, 2, 256, 8)) for _ in range(4))
     mask, pbar = orc.block_mask_bh(q, k, 2, 0.5)
-    assert mask.shape == (1, 2, 2, 4)
-    for h in range(2):
-        m1, p1 = orc.block_mask(q[0, h], k[0, h], 2, 0.5)
-        assert np.array_equal(mask[0, h], m1)
+    assert mask.shape == (2, 2, 2, 4)
+    for b in range(2):
+        for h in range(2):
+            m1, p1 = orc.block_mask(q[b, h], k[b, h], 2, 0.5)
+            assert np.array_equal(mask[b, h], m1)
+            np.testing.assert_array_equal(pbar[b, h], p1)
     o, lse = orc.attention_bh(q, k, v, mask)
     dq, dk, dv, o2, lse2 = orc.attention_bwd_bh(q, k, v, mask, do)
     np.testing.assert_allclose(o, o2, atol=1e-14)
+    e_o, e_lse, _ = orc.attention_definition(q[1, 0], k[1, 0], v[1, 0], mask[1, 0])
+    np.testing.assert_allclose(o2[1, 0], e_o, atol=1e-13)
+    np.testing.assert_allclose(lse2[1, 0], e_lse, atol=1e-13)
+    np.testing.assert_allclose(lse[1, 0], e_lse, atol=1e-13)
     e_dq, e_dk, e_dv = orc.attention_bwd_definition(q[0, 1], k[0, 1], v[0, 1], mask[0, 1], do[0, 1])
     np.testing.assert_allclose(dq[0, 1], e_dq, atol=1e-12)
     np.testing.assert_allclose(dk[0, 1], e_dk, atol=1e-12)
@@ -395,5 +409,14 @@ def test_error_sums_identities():
     o_s, _ = orc.attention_gather(q, k, v, mbar)
     o_f = orc.attention_definition(q, k, v, np.ones_like(mbar))[0]
     assert abs(np.abs(o_f - o_s).sum() - tot) < 1e-9 * max(1.0, tot)
+    assert abs(np.abs(o_f).sum() - ref) < 1e-9 * ref
+    # which part is which: every row keeps the same key blocks, V is 1 on kept tokens and 0 on dropped ones.
+    # Then the dropped weights carry nothing (dropped error 0) and the kept ones, rescaled by 1/tau, give
+    # o_s = 1 against o = tau: the renormalisation error is (tau - 1) in each of the d channels.
+    same = np.zeros_like(mbar); same[:, [0, 3]] = 1
+    vk = np.zeros((n, d)); vk[0:64] = 1.0; vk[192:256] = 1.0
+    tot2, ref2, drop2, ren2, tau2 = orc.error_sums(q, k, vk, same)
+    assert drop2 < 1e-12 and abs(ren2 - d * (n - tau2)) < 1e-9 and abs(tot2 - ren2) < 1e-9
+    assert abs(ref2 - d * tau2) < 1e-9
     full = orc.error_sums(q, k, v, np.ones_like(mbar))
     assert full[0] < 1e-12 and full[2] < 1e-12 and full[3] < 1e-12 and abs(full[4] - n) < 1e-9
