@@ -12,6 +12,7 @@ from oracle import spa2_oracle as orc
 
 MAX_ABS = 2e-2    # tolerance on O, dQ, dK, dV fixed by the benchmark definition (bf16 outputs)
 MEAN_ABS = 2e-3
+REL_L2 = 1.5e-2    # ||got - ref|| / ||ref|| per compared array; measured at most 7e-3 (dQ), 2e-3 (O)
 PBAR_REL = 1e-5   # pooled-map scores: fp32 pooled means, fp64 dot products, fp32 softmax
 CUT_EPS = 1e-5    # rows whose cumulative mass at the cut is this close to p may flip
 
@@ -154,7 +155,7 @@ def mask_protocol(mask_gpu: np.ndarray, pbar_gpu: np.ndarray, pbar_ref: np.ndarr
 BF16_ULP_REL = 2.0 ** -7   # spacing of bf16 numbers relative to the value (worst case, mantissa 1.0)
 
 
-def assert_close(name, got: np.ndarray, ref: np.ndarray, max_abs=MAX_ABS, mean_abs=MEAN_ABS):
+def assert_close(name, got: np.ndarray, ref: np.ndarray, max_abs=MAX_ABS, mean_abs=MEAN_ABS, rel_l2=REL_L2):
     """The benchmark's bar, max-abs <= 2e-2 and mean-abs <= 2e-3, stated for values of order one.
     The path stores bf16 and feeds bf16 P / dS to the second products, so its error is relative to the
     magnitude of what is being summed: a row (one token) of dK whose entries reach 20 cannot be within
@@ -171,4 +172,10 @@ def assert_close(name, got: np.ndarray, ref: np.ndarray, max_abs=MAX_ABS, mean_a
                                 f"exceeds max(2e-2, 2^-7 * row max); max-abs {err.max():.4g}")
     mean_bar = max(mean_abs, 2.0 ** -8 * float(np.abs(ref).mean()))   # rounding to bf16 alone costs about 2^-9.5 * mean|x|
     assert err.mean() <= mean_bar, f"{name}: mean-abs {err.mean():.4g} > {mean_bar:.4g}"
+    # The absolute bar says little where the values themselves are small (long rows of near-uniform weights give
+    # |O| of a few 1e-3), so the error is also bounded relative to the result: two bf16 roundings (P or dS, then
+    # the stored output) give a relative L2 error of about 2e-3; dQ reaches 7e-3 through the cancellation in
+    # dP - D.  A dropped tile, term or factor is ten times the bar or more.
+    rel = float(np.linalg.norm(err) / max(np.linalg.norm(ref), 1e-300))
+    assert rel <= rel_l2, f"{name}: relative L2 error {rel:.3g} > {rel_l2:.3g}"
     return float(err.max()), float(err.mean()), int((err > max_abs).sum())
