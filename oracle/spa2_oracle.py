@@ -21,7 +21,8 @@ What is computed (per batch element and head, independently):
   literal online recurrence) that the tests cross-check;
 * gradients of that map w.r.t. Q, K, V with the mask held constant (the paper
   only says a backward pass exists, Sec. 4.3; this is ordinary softmax
-  calculus).
+  calculus);
+* the velocity distillation loss of Sec. 4.2 and its gradient.
 
 Readings taken where the paper is silent are listed in the repository's design
 notes; the ones that matter here:
@@ -359,6 +360,18 @@ def error_sums(q, k, v, mbar, scale: float | None = None):
         tot += np.abs(o - o_s).sum(); ref += np.abs(o).sum()
         drop += np.abs(dropped).sum(); ren += np.abs(renorm).sum(); tau_sum += tau
     return tot, ref, drop, ren, tau_sum
+
+
+# --------------------------------------------------------------------------
+# Velocity distillation loss (Sec. 4.2 equation; Alg. 2 loss step)
+# --------------------------------------------------------------------------
+def vd_loss(u_sparse, u_full, weight: float):
+    """L_VD = weight * ||u_sparse - u_full||^2 over all elements, and its gradient with respect to the student's
+    prediction, 2 * weight * (u_sparse - u_full).  The paper's expectation over training samples is
+    weight = 1 / (number of samples in the batch); weight = 1 / (number of elements) is the per-element mean."""
+    a = np.asarray(u_sparse, np.float64); b = np.asarray(u_full, np.float64)
+    diff = a - b
+    return float(weight * (diff * diff).sum()), 2.0 * weight * diff
 
 
 # --------------------------------------------------------------------------

@@ -216,6 +216,21 @@ MUTANTS = [
     ('prefix-notreached',
      'reached.argmax(axis=-1) + 1, t_n)',
      'reached.argmax(axis=-1) + 1, 1)'),
+    ('vd-no-square',
+     '(diff * diff).sum()',
+     'np.abs(diff).sum()'),
+    ('vd-grad-sign',
+     '2.0 * weight * diff',
+     '-2.0 * weight * diff'),
+    ('vd-grad-factor',
+     '2.0 * weight * diff',
+     'weight * diff'),
+    ('vd-weight-dropped',
+     'float(weight * (diff * diff).sum())',
+     'float((diff * diff).sum())'),
+    ('vd-sum-not-diff',
+     'diff = a - b',
+     'diff = a + b'),
 ]
 
 

@@ -420,3 +420,27 @@ def test_error_sums_identities():
     assert abs(ref2 - d * tau2) < 1e-9
     full = orc.error_sums(q, k, v, np.ones_like(mbar))
     assert full[0] < 1e-12 and full[2] < 1e-12 and full[3] < 1e-12 and abs(full[4] - n) < 1e-9
+
+
+# ------------------------------------------------------------------ velocity distillation loss
+def test_vd_loss_closed_forms_and_library_gradient():
+    rng = np.random.default_rng(31)
+    u_f = rng.normal(size=(3, 50, 8))
+    # equal predictions: no loss, no gradient; a constant offset c over n elements: weight * n * c^2
+    loss, grad = orc.vd_loss(u_f, u_f, 0.25)
+    assert loss == 0.0 and not grad.any()
+    loss, grad = orc.vd_loss(u_f + 0.5, u_f, 1.0 / 3)                 # three samples of 400 elements
+    assert abs(loss - 400 * 0.25) < 1e-10
+    np.testing.assert_allclose(grad, 2 * 0.5 / 3, rtol=1e-12)
+    # the sign: the gradient points from the teacher to the student
+    u_s = u_f.copy(); u_s[1, 7, 2] += 2.0
+    loss, grad = orc.vd_loss(u_s, u_f, 1.0)
+    assert abs(loss - 4.0) < 1e-12 and abs(grad[1, 7, 2] - 4.0) < 1e-12 and np.count_nonzero(grad) == 1
+    # against the library: mean-squared error and autograd in fp64
+    u_s = rng.normal(size=u_f.shape)
+    ts = torch.tensor(u_s, dtype=torch.float64, requires_grad=True)
+    tl = torch.nn.functional.mse_loss(ts, torch.tensor(u_f, dtype=torch.float64))
+    tl.backward()
+    loss, grad = orc.vd_loss(u_s, u_f, 1.0 / u_s.size)
+    assert abs(loss - tl.item()) < 1e-14
+    np.testing.assert_allclose(grad, ts.grad.numpy(), rtol=1e-13, atol=1e-18)
