@@ -181,6 +181,25 @@ size_t spa2_error_workspace_bytes(const spa2_shape* shape);
 int spa2_error_terms(const void* o_sparse, const void* o_dense, const float* lse_sparse, const float* lse_dense,
                      const spa2_shape* shape, double* out, void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- velocity distillation loss (Sec. 4.2 equation; loss step of Alg. 2) ----
+ *   loss = weight * sum over the n elements of (u_sparse - u_full)^2
+ *   grad = upstream * 2 * weight * (u_sparse - u_full)        (with respect to u_sparse; the teacher is frozen)
+ * The paper's expectation over training samples is weight = 1 / (samples in the batch); 1 / n is the per-element
+ * mean.  u_sparse, u_full, grad: device, contiguous, n elements of `dtype` (bf16 or fp32), 16-byte aligned, caller-
+ * owned; grad may alias neither input.  loss: device, one fp64.  upstream: device, one fp64 (the derivative of the
+ * final objective with respect to loss), or NULL for 1.  The difference is taken in fp32 and the squares are summed
+ * in fp64 in a fixed order: the loss is deterministic.  spa2_vd_loss needs a workspace of
+ * spa2_vd_loss_workspace_bytes() bytes, 16-byte aligned.  Asynchronous on `stream`.
+ * Errors: SPA2_ERR_NULL, _SHAPE (n <= 0), _UNSUPPORTED (dtype), _ALIGN, _RANGE (weight not finite or <= 0),
+ * _WORKSPACE, _LAUNCH; checked before anything is launched. */
+#define SPA2_DTYPE_BF16 0
+#define SPA2_DTYPE_F32  1
+size_t spa2_vd_loss_workspace_bytes(void);
+int spa2_vd_loss(const void* u_sparse, const void* u_full, int64_t n, int32_t dtype, double weight, double* loss,
+                 void* workspace, size_t workspace_bytes, void* stream);
+int spa2_vd_loss_grad(const void* u_sparse, const void* u_full, int64_t n, int32_t dtype, double weight,
+                      const double* upstream /* or NULL */, void* grad, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -88,6 +88,12 @@ def _load():
     lib.spa2_error_workspace_bytes.argtypes = [shp]
     lib.spa2_error_terms.restype = ctypes.c_int
     lib.spa2_error_terms.argtypes = [vp, vp, vp, vp, shp, vp, vp, sz, vp]
+    lib.spa2_vd_loss_workspace_bytes.restype = sz
+    lib.spa2_vd_loss_workspace_bytes.argtypes = []
+    lib.spa2_vd_loss.restype = ctypes.c_int
+    lib.spa2_vd_loss.argtypes = [vp, vp, ctypes.c_int64, i32, ctypes.c_double, vp, vp, sz, vp]
+    lib.spa2_vd_loss_grad.restype = ctypes.c_int
+    lib.spa2_vd_loss_grad.argtypes = [vp, vp, ctypes.c_int64, i32, ctypes.c_double, vp, vp, vp]
     _lib = lib
     return lib
 
@@ -95,7 +101,8 @@ def _load():
 EXPORTED_SYMBOLS = ("spa2_version", "spa2_strerror", "spa2_topk_blocks", "spa2_mask_workspace_bytes",
                     "spa2_bwd_workspace_bytes", "spa2_mask", "spa2_mask_pool", "spa2_mask_select",
                     "spa2_mask_columns", "spa2_pattern_full", "spa2_fwd", "spa2_bwd", "spa2_bwd_delta",
-                    "spa2_bwd_dkdv", "spa2_bwd_dq", "spa2_error_workspace_bytes", "spa2_error_terms")
+                    "spa2_bwd_dkdv", "spa2_bwd_dq", "spa2_error_workspace_bytes", "spa2_error_terms",
+                    "spa2_vd_loss_workspace_bytes", "spa2_vd_loss", "spa2_vd_loss_grad")
 
 
 # ------------------------------------------------------------------ plumbing (memory only)
@@ -290,3 +297,43 @@ def spa2_error_terms(o_sparse: torch.Tensor, o_dense: torch.Tensor, lse_sparse: 
                                   lse_dense.data_ptr(), ctypes.byref(_shape_of(o_sparse)), out.data_ptr(),
                                   workspace.data_ptr(), _nbytes(workspace), _stream(o_sparse))
     _check(rc, "spa2_error_terms")
+
+
+_VD_DTYPES = {torch.bfloat16: 0, torch.float32: 1}
+
+
+def _vd_args(u_sparse: torch.Tensor, u_full: torch.Tensor):
+    if not (u_sparse.is_cuda and u_full.is_cuda):
+        raise ValueError("spa2 runs on the GPU only: predictions must be CUDA tensors")
+    if u_sparse.dtype not in _VD_DTYPES or u_full.dtype != u_sparse.dtype:
+        raise ValueError("predictions are bfloat16 or float32, both of the same type")
+    if u_sparse.shape != u_full.shape or not u_sparse.is_contiguous() or not u_full.is_contiguous():
+        raise ValueError("predictions are contiguous tensors of one shape")
+    return u_sparse.numel(), _VD_DTYPES[u_sparse.dtype]
+
+
+def spa2_vd_loss_workspace_bytes() -> int:
+    return int(_load().spa2_vd_loss_workspace_bytes())
+
+
+def spa2_vd_loss(u_sparse: torch.Tensor, u_full: torch.Tensor, weight: float, loss: torch.Tensor,
+                 workspace: torch.Tensor) -> None:
+    """loss (float64, one element) = weight * sum (u_sparse - u_full)^2."""
+    n, dt = _vd_args(u_sparse, u_full)
+    if loss.dtype != torch.float64 or loss.numel() != 1:
+        raise ValueError("loss is a float64 tensor of one element")
+    _check(_load().spa2_vd_loss(u_sparse.data_ptr(), u_full.data_ptr(), n, dt, float(weight), loss.data_ptr(),
+                                workspace.data_ptr(), _nbytes(workspace), _stream(u_sparse)), "spa2_vd_loss")
+
+
+def spa2_vd_loss_grad(u_sparse: torch.Tensor, u_full: torch.Tensor, weight: float, upstream: Optional[torch.Tensor],
+                      grad: torch.Tensor) -> None:
+    """grad = upstream * 2 * weight * (u_sparse - u_full); upstream is a float64 device scalar or None (= 1)."""
+    n, dt = _vd_args(u_sparse, u_full)
+    if grad.dtype != u_sparse.dtype or grad.shape != u_sparse.shape or not grad.is_contiguous():
+        raise ValueError("grad has the type and shape of the predictions and is contiguous")
+    if upstream is not None and (upstream.dtype != torch.float64 or upstream.numel() != 1 or not upstream.is_cuda):
+        raise ValueError("upstream is a float64 CUDA tensor of one element")
+    _check(_load().spa2_vd_loss_grad(u_sparse.data_ptr(), u_full.data_ptr(), n, dt, float(weight),
+                                     None if upstream is None else upstream.data_ptr(), grad.data_ptr(),
+                                     _stream(u_sparse)), "spa2_vd_loss_grad")

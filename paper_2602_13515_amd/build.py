@@ -15,7 +15,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 BUILD = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libspa2.so")
-SOURCES = ["api.hip", "mask.hip", "fwd.hip", "bwd.hip", "diag.hip"]
+SOURCES = ["api.hip", "mask.hip", "fwd.hip", "bwd.hip", "diag.hip", "distill.hip"]
 
 HIPCC = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
 FLAGS = [

@@ -47,9 +47,9 @@ const char* spa2_strerror(int code) {
     case SPA2_OK: return "ok";
     case SPA2_ERR_NULL: return "a required pointer is NULL";
     case SPA2_ERR_SHAPE: return "invalid shape or strides";
-    case SPA2_ERR_UNSUPPORTED: return "unsupported head dimension or block size (d must be 64 or 128, blocks 128x64)";
+    case SPA2_ERR_UNSUPPORTED: return "unsupported head dimension, block size or element type (d must be 64 or 128, blocks 128x64)";
     case SPA2_ERR_ALIGN: return "pointer not 16-byte aligned or stride not a multiple of 8 elements";
-    case SPA2_ERR_RANGE: return "parameter out of range (topk_blocks in [0,T_n], top_p in [0,1], not both zero, scale > 0)";
+    case SPA2_ERR_RANGE: return "parameter out of range (topk_blocks in [0,T_n], top_p in [0,1], not both zero, scale > 0, weight > 0)";
     case SPA2_ERR_WORKSPACE: return "workspace missing or too small";
     case SPA2_ERR_LAUNCH: return "kernel launch failed";
     default: return "unknown spa2 error code";
@@ -252,5 +252,37 @@ int spa2_error_terms(const void* o_sparse, const void* o_dense, const float* lse
   if (!workspace || workspace_bytes < error_ws_bytes(m)) return SPA2_ERR_WORKSPACE;
   return launch_error_terms(o_sparse, o_dense, lse_sparse, lse_dense, m, out, workspace, (hipStream_t)stream) == hipSuccess
              ? SPA2_OK : SPA2_ERR_LAUNCH;
+}
+
+size_t spa2_vd_loss_workspace_bytes(void) { return round256(vd_ws_bytes()); }
+
+static int check_vd(const void* u_sparse, const void* u_full, int64_t n, int32_t dtype, double weight) {
+  if (!u_sparse || !u_full) return SPA2_ERR_NULL;
+  if (n <= 0) return SPA2_ERR_SHAPE;
+  if (dtype != SPA2_DTYPE_BF16 && dtype != SPA2_DTYPE_F32) return SPA2_ERR_UNSUPPORTED;
+  if (!aligned16(u_sparse) || !aligned16(u_full)) return SPA2_ERR_ALIGN;
+  if (!(weight > 0.0) || !isfinite(weight)) return SPA2_ERR_RANGE;
+  return SPA2_OK;
+}
+
+int spa2_vd_loss(const void* u_sparse, const void* u_full, int64_t n, int32_t dtype, double weight, double* loss,
+                 void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_vd(u_sparse, u_full, n, dtype, weight);
+  if (rc != SPA2_OK) return rc;
+  if (!loss) return SPA2_ERR_NULL;
+  if (!workspace || workspace_bytes < vd_ws_bytes()) return SPA2_ERR_WORKSPACE;
+  if (!aligned16(workspace)) return SPA2_ERR_ALIGN;
+  return launch_vd_loss(u_sparse, u_full, n, dtype == SPA2_DTYPE_BF16, weight, loss, workspace, (hipStream_t)stream) ==
+                 hipSuccess ? SPA2_OK : SPA2_ERR_LAUNCH;
+}
+
+int spa2_vd_loss_grad(const void* u_sparse, const void* u_full, int64_t n, int32_t dtype, double weight,
+                      const double* upstream, void* grad, void* stream) {
+  int rc = check_vd(u_sparse, u_full, n, dtype, weight);
+  if (rc != SPA2_OK) return rc;
+  if (!grad) return SPA2_ERR_NULL;
+  if (!aligned16(grad)) return SPA2_ERR_ALIGN;
+  return launch_vd_grad(u_sparse, u_full, n, dtype == SPA2_DTYPE_BF16, weight, upstream, grad, (hipStream_t)stream) ==
+                 hipSuccess ? SPA2_OK : SPA2_ERR_LAUNCH;
 }
 }  // extern "C"

@@ -47,4 +47,10 @@ size_t error_ws_bytes(const Dims& m);
 hipError_t launch_error_terms(const void* o_sparse, const void* o_dense, const float* lse_sparse,
                               const float* lse_dense, const Dims& m, double* out, void* ws, hipStream_t stream);
 
+size_t vd_ws_bytes();
+hipError_t launch_vd_loss(const void* u_sparse, const void* u_full, int64_t n, bool bf16, double weight, double* loss,
+                          void* ws, hipStream_t stream);
+hipError_t launch_vd_grad(const void* u_sparse, const void* u_full, int64_t n, bool bf16, double weight,
+                          const double* upstream, void* grad, hipStream_t stream);
+
 }  // namespace spa2

@@ -62,9 +62,41 @@ def noisy_latent(x1: torch.Tensor, x0: torch.Tensor, t: torch.Tensor) -> torch.T
     return t * x1 + (1.0 - t) * x0
 
 
-def velocity_distillation_loss(u_sparse: torch.Tensor, u_full: torch.Tensor) -> torch.Tensor:
-    """L_VD = ||u_sparse - u_full||^2, averaged over the batch and the elements (Sec. 4.2)."""
-    return (u_sparse.float() - u_full.float()).square().mean()
+class _VelocityDistillationLoss(torch.autograd.Function):
+    """weight * ||u_sparse - u_full||^2 through the fused kernels: one pass for the loss, one for the gradient."""
+
+    @staticmethod
+    def forward(ctx, u_sparse, u_full, weight):
+        u_full = u_full.detach()
+        loss = torch.empty((), dtype=torch.float64, device=u_sparse.device)
+        ws = torch.empty(_b.spa2_vd_loss_workspace_bytes(), dtype=torch.uint8, device=u_sparse.device)
+        _b.spa2_vd_loss(u_sparse.detach(), u_full, weight, loss, ws)
+        ctx.save_for_backward(u_sparse, u_full)
+        ctx.weight = weight
+        return loss
+
+    @staticmethod
+    def backward(ctx, upstream):
+        u_sparse, u_full = ctx.saved_tensors
+        grad = torch.empty_like(u_sparse)
+        _b.spa2_vd_loss_grad(u_sparse.detach(), u_full, ctx.weight, upstream.contiguous(), grad)
+        return grad, None, None
+
+
+def velocity_distillation_loss(u_sparse: torch.Tensor, u_full: torch.Tensor, reduction: str = "mean") -> torch.Tensor:
+    """L_VD = ||u_sparse - u_full||^2 (Sec. 4.2; Alg. 2), a float64 scalar.  `reduction`: "mean" divides by the
+    number of elements; "batch" divides by the size of the leading dimension, which is the paper's expectation over
+    training samples of the squared norm.  The teacher's prediction gets no gradient (it is frozen)."""
+    if reduction == "mean":
+        weight = 1.0 / u_sparse.numel()
+    elif reduction == "batch":
+        weight = 1.0 / u_sparse.shape[0]
+    else:
+        raise ValueError('reduction is "mean" or "batch"')
+    if not u_sparse.is_cuda:
+        raise ValueError("spa2 runs on the GPU only: predictions must be CUDA tensors")
+    u_full = u_full.to(u_sparse.dtype)
+    return _VelocityDistillationLoss.apply(u_sparse.contiguous(), u_full.contiguous(), weight)
 
 
 def distill(student: torch.nn.Module, teacher: torch.nn.Module, batches: Iterable[Tuple[torch.Tensor, torch.Tensor, torch.Tensor]],

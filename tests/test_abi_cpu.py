@@ -93,6 +93,18 @@ def test_argument_validation_happens_on_the_host():
     assert b(*args, ctypes.byref(ok), ctypes.byref(norows), 0.1, fake, fake, fake, fake, big, None) == -1
     assert b(*args, ctypes.byref(ok), ctypes.byref(full), 0.1, fake, fake, fake, fake, 8, None) == -6
     assert lib.spa2_pattern_full(ctypes.byref(ok), None, None) == -1
+    vd, vg = lib.spa2_vd_loss, lib.spa2_vd_loss_grad
+    assert vd(None, fake, 8, 0, 1.0, fake, fake, big, None) == -1
+    assert vd(fake, fake, 0, 0, 1.0, fake, fake, big, None) == -2
+    assert vd(fake, fake, 8, 2, 1.0, fake, fake, big, None) == -3            # element type
+    assert vd(odd, fake, 8, 1, 1.0, fake, fake, big, None) == -4
+    assert vd(fake, fake, 8, 1, 0.0, fake, fake, big, None) == -5
+    assert vd(fake, fake, 8, 1, float("inf"), fake, fake, big, None) == -5
+    assert vd(fake, fake, 8, 1, 1.0, fake, fake, 64, None) == -6
+    assert vd(fake, fake, 8, 1, 1.0, None, fake, big, None) == -1
+    assert vg(fake, fake, 8, 1, 1.0, None, None, None) == -1
+    assert vg(fake, fake, 8, 1, 1.0, None, odd, None) == -4
+    assert lib.spa2_vd_loss_workspace_bytes() >= 2048 * 8
 
 
 def test_workspace_sizes():
