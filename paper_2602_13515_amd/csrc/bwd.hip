@@ -24,30 +24,39 @@ struct DeltaArgs {
 template <int D>
 __global__ __launch_bounds__(256) void delta_kernel(DeltaArgs a) {
   constexpr int LPR = D / 8, RP = 256 / LPR;
+  constexpr int NIT = 4;              // row groups per workgroup; all their loads are issued before the first use
   const int bh = blockIdx.y;
   const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
   const int tid = threadIdx.x;
   const int col = (tid % LPR) * 8;
+  u32x4 x[NIT], y[NIT], z[NIT];
+  int row[NIT];
 #pragma unroll
-  for (int it = 0; it < 4; ++it) {
-    const int row = (blockIdx.x * 4 + it) * RP + tid / LPR;
+  for (int it = 0; it < NIT; ++it) {
+    row[it] = (blockIdx.x * NIT + it) * RP + tid / LPR;
+    const int64_t off = base + (int64_t)min(row[it], a.N - 1) * a.sn + col;   // rows past the end: clamped, not stored
+    x[it] = *(const u32x4*)(a.o + off);
+    y[it] = *(const u32x4*)(a.d_o + off);
+    z[it] = u32x4{0, 0, 0, 0};
+  }
+  if (a.o_res) {
+#pragma unroll
+    for (int it = 0; it < NIT; ++it)
+      z[it] = *(const u32x4*)(a.o_res + base + (int64_t)min(row[it], a.N - 1) * a.sn + col);
+  }
+#pragma unroll
+  for (int it = 0; it < NIT; ++it) {
     float s = 0.f;
-    if (row < a.N) {
-      const u32x4 x = *(const u32x4*)(a.o + base + (int64_t)row * a.sn + col);
-      const u32x4 y = *(const u32x4*)(a.d_o + base + (int64_t)row * a.sn + col);
-      u32x4 z = u32x4{0, 0, 0, 0};
-      if (a.o_res) z = *(const u32x4*)(a.o_res + base + (int64_t)row * a.sn + col);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const float o0 = __builtin_bit_cast(float, x[e] << 16) + __builtin_bit_cast(float, z[e] << 16);
-        const float o1 = __builtin_bit_cast(float, x[e] & 0xffff0000u) + __builtin_bit_cast(float, z[e] & 0xffff0000u);
-        s = fmaf(o0, __builtin_bit_cast(float, y[e] << 16), s);
-        s = fmaf(o1, __builtin_bit_cast(float, y[e] & 0xffff0000u), s);
-      }
+    for (int e = 0; e < 4; ++e) {
+      const float o0 = __builtin_bit_cast(float, x[it][e] << 16) + __builtin_bit_cast(float, z[it][e] << 16);
+      const float o1 = __builtin_bit_cast(float, x[it][e] & 0xffff0000u) + __builtin_bit_cast(float, z[it][e] & 0xffff0000u);
+      s = fmaf(o0, __builtin_bit_cast(float, y[it][e] << 16), s);
+      s = fmaf(o1, __builtin_bit_cast(float, y[it][e] & 0xffff0000u), s);
     }
 #pragma unroll
     for (int off = LPR / 2; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
-    if (row < a.N && (tid % LPR) == 0) a.delta[(int64_t)bh * a.N + row] = s;
+    if (row[it] < a.N && (tid % LPR) == 0) a.delta[(int64_t)bh * a.N + row[it]] = s;
   }
 }
 

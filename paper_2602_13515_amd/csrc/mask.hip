@@ -23,6 +23,30 @@ struct PoolArgs {
   int64_t sb, sh, sn;
 };
 
+// Sum of the valid token rows of one block, as 8 channels per thread.  All loads of the block are issued before
+// the first add (rows past the end are clamped to the last valid row and not added), so a wave keeps LEN / RP
+// 16-byte requests in flight instead of one.
+template <int D, int LEN>
+__device__ __forceinline__ void pool_rows(const uint16_t* x, int64_t sn, int tok0, int valid, int rsub, int col,
+                                          float (&acc)[8]) {
+  constexpr int RP = 256 / (D / 8);   // token rows per pass
+  constexpr int NP = LEN / RP;
+  u32x4 raw[NP];
+#pragma unroll
+  for (int p = 0; p < NP; ++p) raw[p] = *(const u32x4*)(x + (int64_t)(tok0 + min(rsub + p * RP, valid - 1)) * sn + col);
+#pragma unroll
+  for (int p = 0; p < NP; ++p) {
+    const bool live = rsub + p * RP < valid;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float lo = __builtin_bit_cast(float, raw[p][e] << 16);
+      const float hi = __builtin_bit_cast(float, raw[p][e] & 0xffff0000u);
+      acc[2 * e] += live ? lo : 0.f;
+      acc[2 * e + 1] += live ? hi : 0.f;
+    }
+  }
+}
+
 template <int D>
 __global__ __launch_bounds__(256) void pool_kernel(PoolArgs a) {
   constexpr int LPR = D / 8;          // lanes per token row (16 bytes each)
@@ -43,17 +67,8 @@ __global__ __launch_bounds__(256) void pool_kernel(PoolArgs a) {
   float acc[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) acc[e] = 0.f;
-#pragma unroll 4
-  for (int r = rsub; r < len; r += RP) {
-    if (r < valid) {
-      const u32x4 raw = *(const u32x4*)(x + (int64_t)(tok0 + r) * a.sn + col);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        acc[2 * e] += __builtin_bit_cast(float, raw[e] << 16);
-        acc[2 * e + 1] += __builtin_bit_cast(float, raw[e] & 0xffff0000u);
-      }
-    }
-  }
+  if (is_q) pool_rows<D, BQ>(x, a.sn, tok0, valid, rsub, col, acc);
+  else      pool_rows<D, BKV>(x, a.sn, tok0, valid, rsub, col, acc);
 #pragma unroll
   for (int e = 0; e < 8; ++e) red[rsub][col + e] = acc[e];
   __syncthreads();
