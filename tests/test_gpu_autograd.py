@@ -65,3 +65,26 @@ def test_operator_reuses_a_given_pattern_and_rejects_cpu_tensors():
     assert_close("O dense", f64(o), ref.numpy())
     with pytest.raises(ValueError):
         spa2.sparge_attn2(q.cpu(), k.cpu(), v.cpu(), 0.1, 0.5)
+
+
+def test_two_stream_backward_gives_the_same_bits():
+    """dK/dV and dQ kernels launched at the same time on two streams: same gradients as back to back, also when
+    the call is repeated while the side stream still holds work from the previous one."""
+    w = wl.Workload("op2", 1, 3, 2100, 128, 0.2, 0.8, "lowrank", True)
+    q, k, v, do = (t.to(dev()) for t in wl.make_inputs(w, seed=9))
+    grads = {}
+    pat = None
+    for overlap in (False, True, True):
+        qg, kg, vg = (t.clone().requires_grad_(True) for t in (q, k, v))
+        o, pat = spa2.sparge_attn2(qg, kg, vg, w.k_frac, w.top_p, pattern=pat, return_pattern=True,
+                                   overlap_backward=overlap)
+        (o.float() * do.float()).sum().backward()
+        torch.cuda.synchronize()
+        got = (qg.grad.clone(), kg.grad.clone(), vg.grad.clone())
+        if not overlap:
+            grads = got
+        else:
+            for name, a, b in zip(("dQ", "dK", "dV"), got, grads):
+                assert torch.equal(a, b), name
+    r_dq, r_dk, r_dv, _, _ = _oracle(q, k, v, do, pat.mask.cpu().numpy())
+    assert_close("dQ", f64(grads[0]), r_dq, max_abs=5e-2); assert_close("dK", f64(grads[1]), r_dk); assert_close("dV", f64(grads[2]), r_dv)
