@@ -162,6 +162,7 @@ __global__ __launch_bounds__(256) void select_kernel(SelArgs a) {
   static_assert(R == 4, "one wave scans the histogram of one row");
   constexpr int JJ = NP / 256;            // score columns per thread per row
   constexpr int G = score_group(JJ);      // columns per thread processed together in the score loop (divides JJ)
+  constexpr int CB = G <= 4 ? 8 : 4;      // channels whose loads are in flight together (CB * G requests per lane)
   constexpr int E = R * NP / 256;         // consecutive block indices per thread in the compaction pass
   constexpr int SEG_T = 256 / R;          // threads per row in the compaction pass
   __shared__ uint32_t h_cnt[R][256];
@@ -200,16 +201,28 @@ __global__ __launch_bounds__(256) void select_kernel(SelArgs a) {
 #pragma unroll
       for (int u = 0; u < G; ++u) acc[r][u] = 0.0;
     if (tid + 256 * jg < Tn) {       // whole groups past the end of the row are skipped
-      for (int c = 0; c < d; ++c) {
-        double q4[R];
+      int jc[G];                     // this thread's columns of the group, clamped to the row
 #pragma unroll
-        for (int r = 0; r < R; ++r) q4[r] = qd[c][r];
+      for (int u = 0; u < G; ++u) jc[u] = min(tid + 256 * (jg + u), Tn - 1);
+      // CB channels at a time: their CB * G loads are issued together, then the products are added channel by
+      // channel, so every accumulator still sums c = 0, 1, 2, ... in order (d is a multiple of 64)
+      for (int c0 = 0; c0 < d; c0 += CB) {
+        float kraw[CB][G];
 #pragma unroll
-        for (int u = 0; u < G; ++u) {
-          const int j = tid + 256 * (jg + u);
-          const double kv = (double)kt[(int64_t)c * a.TnP + min(j, Tn - 1)];
+        for (int cc = 0; cc < CB; ++cc)
 #pragma unroll
-          for (int r = 0; r < R; ++r) acc[r][u] = fma(q4[r], kv, acc[r][u]);
+          for (int u = 0; u < G; ++u) kraw[cc][u] = kt[(int64_t)(c0 + cc) * a.TnP + jc[u]];
+#pragma unroll
+        for (int cc = 0; cc < CB; ++cc) {
+          double q4[R];
+#pragma unroll
+          for (int r = 0; r < R; ++r) q4[r] = qd[c0 + cc][r];
+#pragma unroll
+          for (int u = 0; u < G; ++u) {
+            const double kv = (double)kraw[cc][u];
+#pragma unroll
+            for (int r = 0; r < R; ++r) acc[r][u] = fma(q4[r], kv, acc[r][u]);
+          }
         }
       }
     }
