@@ -14,8 +14,9 @@
  *
  * Conventions common to every entry point
  *   - Every tensor pointer is a DEVICE pointer owned by the caller.  The
- *     library never allocates, frees or keeps device memory and holds no
- *     global state.  bf16 tensors are raw 16-bit storage.
+ *     library never allocates or frees device memory and keeps nothing between
+ *     calls (the one exception, a fixed scratch array, is described at
+ *     spa2_bwd_static).  bf16 tensors are raw 16-bit storage.
  *   - Calls enqueue work on `stream` (a hipStream_t passed as void*; NULL is
  *     the default stream) and return without synchronising.
  *   - Return value: SPA2_OK (0) or a negative SPA2_ERR_* code.  All argument
@@ -165,6 +166,20 @@ int spa2_bwd_dkdv(const void* q, const void* k, const void* v, const void* d_o, 
 int spa2_bwd_dq(const void* q, const void* k, const void* v, const void* d_o, const float* lse,
                 const spa2_shape* shape, const spa2_pattern* pattern, float scale,
                 void* dq, const void* workspace, size_t workspace_bytes, void* stream);
+
+/* spa2_bwd for callers that cannot provide or allocate a workspace (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): same arguments, results and error behaviour as spa2_bwd, without the
+ * workspace.  D is kept in a fixed array of SPA2_STATIC_MAX_ROWS floats (16 MiB) that the library holds in the
+ * memory of every GPU it runs on until the process ends; no allocation happens in this call (the array's device
+ * address is looked up on the first call on each device, with the calling thread's current device).
+ *   Limit: B * H * N <= SPA2_STATIC_MAX_ROWS, otherwise SPA2_ERR_WORKSPACE and nothing is launched.
+ *   All calls on one GPU share that array: two calls whose execution overlaps on one GPU (different streams,
+ *   different threads) race on D and give wrong gradients; calls on one stream are safe.  The array keeps the
+ *   last call's D; every row a call reads is written by that same call first. */
+#define SPA2_STATIC_MAX_ROWS (4 * 1024 * 1024)
+int spa2_bwd_static(const void* q, const void* k, const void* v, const void* o, const void* o_res /* or NULL */,
+                    const void* d_o, const float* lse, const spa2_shape* shape, const spa2_pattern* pattern,
+                    float scale, void* dq, void* dk, void* dv, void* stream);
 
 /* ---- diagnostics: the error of sparse attention and its two parts (Sec. 3.1) ----
  * For every query row, with tau = exp(lse_sparse - lse_dense) the attention mass the mask retains:

@@ -72,6 +72,8 @@ def _load():
     lib.spa2_fwd.argtypes = [vp, vp, vp, shp, pat, f32, vp, vp, vp, vp]
     lib.spa2_bwd.restype = ctypes.c_int
     lib.spa2_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, shp, pat, f32, vp, vp, vp, vp, sz, vp]
+    lib.spa2_bwd_static.restype = ctypes.c_int
+    lib.spa2_bwd_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, shp, pat, f32, vp, vp, vp, vp]
     lib.spa2_mask_pool.restype = ctypes.c_int
     lib.spa2_mask_pool.argtypes = [vp, vp, shp, vp, sz, vp]
     lib.spa2_mask_select.restype = ctypes.c_int
@@ -100,7 +102,7 @@ def _load():
 
 EXPORTED_SYMBOLS = ("spa2_version", "spa2_strerror", "spa2_topk_blocks", "spa2_mask_workspace_bytes",
                     "spa2_bwd_workspace_bytes", "spa2_mask", "spa2_mask_pool", "spa2_mask_select",
-                    "spa2_mask_columns", "spa2_pattern_full", "spa2_fwd", "spa2_bwd", "spa2_bwd_delta",
+                    "spa2_mask_columns", "spa2_pattern_full", "spa2_fwd", "spa2_bwd", "spa2_bwd_static", "spa2_bwd_delta",
                     "spa2_bwd_dkdv", "spa2_bwd_dq", "spa2_error_workspace_bytes", "spa2_error_terms",
                     "spa2_vd_loss_workspace_bytes", "spa2_vd_loss", "spa2_vd_loss_grad")
 
@@ -226,6 +228,24 @@ def spa2_bwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, o: torch.Tensor,
                           dv.data_ptr(), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                           _stream(q))
     _check(rc, "spa2_bwd")
+
+
+STATIC_MAX_ROWS = 4 * 1024 * 1024   # SPA2_STATIC_MAX_ROWS of the header
+
+
+def spa2_bwd_static(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, o: torch.Tensor, d_o: torch.Tensor,
+                    lse: torch.Tensor, pattern: Pattern, scale: float, dq: torch.Tensor, dk: torch.Tensor,
+                    dv: torch.Tensor, o_res: Optional[torch.Tensor] = None) -> None:
+    """spa2_bwd without a workspace: D lives in the library's fixed per-GPU array (B*H*N <= STATIC_MAX_ROWS)."""
+    _same_layout(q, k, v, o, d_o, dq, dk, dv, *([o_res] if o_res is not None else []))
+    shape = _shape_of(q)
+    pat = pattern._c()
+    with torch.cuda.device(q.device):      # the library looks its array up on the current device
+        rc = _load().spa2_bwd_static(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(),
+                                     o_res.data_ptr() if o_res is not None else None, d_o.data_ptr(),
+                                     lse.data_ptr(), ctypes.byref(shape), ctypes.byref(pat), float(scale),
+                                     dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), _stream(q))
+    _check(rc, "spa2_bwd_static")
 
 
 # ------------------------------------------------------------------ the stages of spa2_mask / spa2_bwd, one by one

@@ -1,6 +1,9 @@
 // C ABI of spa2: argument validation, workspace layout, kernel sequencing.
-// No device memory is allocated here and nothing is kept between calls.
+// No device memory is allocated here.  Nothing is kept between calls except the per-device address of the
+// fixed scratch array that spa2_bwd_static uses (looked up once per device).
 #include <math.h>
+
+#include <mutex>
 
 #include "spa2_internal.h"
 
@@ -286,3 +289,45 @@ int spa2_vd_loss_grad(const void* u_sparse, const void* u_full, int64_t n, int32
                  hipSuccess ? SPA2_OK : SPA2_ERR_LAUNCH;
 }
 }  // extern "C"
+
+// ---------------------------------------------------------------- spa2_bwd without a workspace argument
+// D = rowsum(dO * O) (fp32, one value per token row) lives in a fixed array in device memory instead of a
+// caller's workspace.  The array's name is only a host-side handle: its device address differs per GPU and is
+// looked up once per device with that device current; kernels and every other use take that address.
+namespace {
+
+__device__ __align__(256) float scratch[SPA2_STATIC_MAX_ROWS];
+
+constexpr int MAX_DEVICES = 64;
+float* scratch_ptr[MAX_DEVICES];     // per device, nullptr until looked up
+std::mutex scratch_mutex;
+
+int scratch_for_current_device(float** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return SPA2_ERR_LAUNCH;
+  std::lock_guard<std::mutex> lock(scratch_mutex);
+  if (!scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return SPA2_ERR_LAUNCH;
+    scratch_ptr[dev] = (float*)p;
+  }
+  *out = scratch_ptr[dev];
+  return SPA2_OK;
+}
+
+}  // namespace
+
+extern "C" int spa2_bwd_static(const void* q, const void* k, const void* v, const void* o, const void* o_res,
+                               const void* d_o, const float* lse, const spa2_shape* shape,
+                               const spa2_pattern* pattern, float scale, void* dq, void* dk, void* dv,
+                               void* stream) {
+  int rc = check_shape(shape);
+  if (rc != SPA2_OK) return rc;
+  if ((int64_t)shape->B * shape->H * shape->N > (int64_t)SPA2_STATIC_MAX_ROWS) return SPA2_ERR_WORKSPACE;
+  float* ws = nullptr;
+  rc = scratch_for_current_device(&ws);
+  if (rc != SPA2_OK) return rc;
+  // every row of D that the kernels read is written by the delta pass of this same call: nothing to clear
+  return spa2_bwd(q, k, v, o, o_res, d_o, lse, shape, pattern, scale, dq, dk, dv, ws,
+                  (size_t)SPA2_STATIC_MAX_ROWS * sizeof(float), stream);
+}
