@@ -24,6 +24,9 @@ int check_shape(const spa2_shape* s) {
   // the kernels address a tile as a 64-bit base plus a 32-bit byte offset of up to 128 token rows
   if (s->sn > SPA2_MAX_TOKEN_STRIDE) return SPA2_ERR_SHAPE;
   if ((int64_t)s->B * s->H > (int64_t)1 << 24) return SPA2_ERR_SHAPE;
+  // one-dimensional grids of up to B*H*(T_m + T_n + 16) workgroups, 32-bit workgroup arithmetic in the kernels
+  const int64_t tm = ((int64_t)s->N + SPA2_BQ - 1) / SPA2_BQ, tn = ((int64_t)s->N + SPA2_BKV - 1) / SPA2_BKV;
+  if ((int64_t)s->B * s->H * (tm + tn + 16) > (int64_t)0x7fffffff) return SPA2_ERR_SHAPE;
   return SPA2_OK;
 }
 
@@ -117,6 +120,7 @@ int spa2_mask_columns(const spa2_shape* shape, spa2_pattern* out, void* stream) 
   if (rc != SPA2_OK) return rc;
   if (!out || !out->mask || !out->col_cnt || !out->col_idx) return SPA2_ERR_NULL;
   const Dims m = make_dims(*shape);
+  if (m.Tn > SPA2_MAX_TN) return SPA2_ERR_SHAPE;     // the column sort holds one head's T_n keys in LDS
   return launch_columns(out->mask, m, out->col_cnt, out->col_idx, out->col_order, (hipStream_t)stream) == hipSuccess
              ? SPA2_OK : SPA2_ERR_LAUNCH;
 }

@@ -85,6 +85,18 @@ def test_argument_validation_happens_on_the_host():
     assert m(fake, fake, ctypes.byref(ok), 1, float("nan"), 0.1, ctypes.byref(full), None, fake, big, None) == -5
     assert m(fake, fake, ctypes.byref(_shape(N=64 * 8193, d=64)), 1, 0.5, 0.1, ctypes.byref(full), None, fake,
              1 << 40, None) == -2                                                                      # row too long
+    # spa2_mask_columns alone refuses rows longer than its sort holds (N > 524,288), like spa2_mask does
+    assert lib.spa2_mask_columns(ctypes.byref(_shape(N=64 * 8193, d=64)), ctypes.byref(full), None) == -2
+    # B*H*(T_m + T_n) workgroups must fit a 32-bit grid: 2^24 heads of 20,000 tokens do not
+    many = _shape(B=1 << 12, H=1 << 12, N=20000, d=64)
+    assert lib.spa2_mask_columns(ctypes.byref(many), ctypes.byref(full), None) == -2
+    assert f(fake, fake, fake, ctypes.byref(many), ctypes.byref(full), 0.1, fake, None, fake, None) == -2
+    # the workspace-free backward: same checks, and its fixed array bounds B*H*N
+    bs = lib.spa2_bwd_static
+    sargs = [fake, fake, fake, fake, None, fake, fake]
+    assert bs(*sargs, None, ctypes.byref(full), 0.1, fake, fake, fake, None) == -1
+    too_long = _shape(B=1, H=4, N=binding.STATIC_MAX_ROWS // 4 + 64, d=128)
+    assert bs(*sargs, ctypes.byref(too_long), ctypes.byref(full), 0.1, fake, fake, fake, None) == -6
     half = binding._Pattern(0x1000, 0x1000, 0x1000, 0x1000, None)
     assert m(fake, fake, ctypes.byref(ok), 1, 0.5, 0.1, ctypes.byref(half), None, fake, big, None) == -1
     b = lib.spa2_bwd
@@ -195,3 +207,37 @@ def test_header_is_plain_c():
         r = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only",
                             "-I", os.path.join(ROOT, "include"), src], capture_output=True, text=True)
         assert r.returncode == 0, r.stderr
+
+
+def test_argument_checks_under_host_sanitizers():
+    """The argument-check layer (csrc/api.hip) compiled with AddressSanitizer and UndefinedBehaviorSanitizer on the
+    host side, linked against launcher stubs that abort, and driven by tests/abi_sanitize/driver.c with every kind
+    of rejected call: no sanitizer report, no launcher reached, every error code as documented."""
+    import shutil
+    import subprocess
+    import tempfile
+    hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    clang = "/opt/rocm/lib/llvm/bin/clang"
+    if not (os.path.exists(hipcc) and os.path.exists(clang)):
+        pytest.skip("no ROCm toolchain")
+    inc = ["-I", os.path.join(ROOT, "include"), "-I", os.path.join(ROOT, "paper_2602_13515_amd", "csrc")]
+    san = ["-fsanitize=address", "-fsanitize=undefined", "-fno-sanitize-recover=undefined"]
+    xsan = [x for s in san for x in ("-Xarch_host", s)]
+    dev = ["--offload-arch=gfx950", "-O1", "-g", "-std=c++17", "-Wno-unused-command-line-argument",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+    here = os.path.join(ROOT, "tests", "abi_sanitize")
+    with tempfile.TemporaryDirectory() as td:
+        o = lambda n: os.path.join(td, n)
+        steps = [
+            [clang, "-std=c99", "-g", "-c", *san, *inc, os.path.join(here, "driver.c"), "-o", o("driver.o")],
+            [hipcc, *dev, *xsan, *inc, "-c", os.path.join(ROOT, "paper_2602_13515_amd", "csrc", "api.hip"), "-o", o("api.o")],
+            [hipcc, *dev, *xsan, *inc, "-x", "hip", "-c", os.path.join(here, "launch_stubs.cpp"), "-o", o("stubs.o")],
+            [hipcc, "--offload-arch=gfx950", "-fsanitize=address", "-fsanitize=undefined", "-fno-gpu-sanitize",
+             o("api.o"), o("stubs.o"), o("driver.o"), "-o", o("abi_check")],
+        ]
+        for cmd in steps:
+            r = subprocess.run(cmd, capture_output=True, text=True)
+            assert r.returncode == 0, r.stderr[-3000:]
+        r = subprocess.run([o("abi_check")], capture_output=True, text=True, timeout=120)
+        assert r.returncode == 0 and "all rejected before launch" in r.stdout, (r.stdout[-2000:], r.stderr[-3000:])
+        assert "runtime error" not in r.stderr and "AddressSanitizer" not in r.stderr, r.stderr[-3000:]
