@@ -11,13 +11,13 @@ import paper_2602_13515_amd as spa2
 from oracle import spa2_oracle as orc
 from paper_2602_13515_amd import workloads as wl
 
-from gpu_util import MAX_ABS, MEAN_ABS, assert_close, dev, f64, mask_protocol
+from gpu_util import LOWRANK_MAX_ABS, MAX_ABS, MEAN_ABS, assert_close, dev, f64, mask_protocol
 
 pytestmark = pytest.mark.gpu
 
 
 def _run_path(w, q, k, v, do, k_frac=None, top_p=None, want_pbar=True):
-    """mask -> fwd -> bwd exactly as bench.py sequences them."""
+    """mask -> fwd -> bwd exactly as bench.py sequences them (forward only when the workload has no backward)."""
     k_frac = w.k_frac if k_frac is None else k_frac
     top_p = w.top_p if top_p is None else top_p
     scale = 1.0 / math.sqrt(w.d)
@@ -28,49 +28,91 @@ def _run_path(w, q, k, v, do, k_frac=None, top_p=None, want_pbar=True):
     ws_b = torch.empty(spa2.spa2_bwd_workspace_bytes(q), dtype=torch.uint8, device=q.device)
     o = torch.full_like(q, float("nan")); lse = torch.empty((w.B, w.H, w.N), dtype=torch.float32, device=q.device)
     o_res = torch.full_like(q, float("nan"))
-    dq = torch.full_like(q, float("nan")); dk = torch.full_like(q, float("nan")); dv = torch.full_like(q, float("nan"))
     spa2.spa2_mask_pool(q, k, ws_m)
     spa2.spa2_mask_select(q, k_cnt, top_p, scale, pat, pbar, ws_m)
     spa2.spa2_mask_columns(q, pat)
     spa2.spa2_fwd(q, k, v, pat, scale, o, lse, o_res)
-    spa2.spa2_bwd_delta(o, do, ws_b, o_res)
-    spa2.spa2_bwd_dkdv(q, k, v, do, lse, pat, scale, dk, dv, ws_b)
-    spa2.spa2_bwd_dq(q, k, v, do, lse, pat, scale, dq, ws_b)
+    dq = dk = dv = None
+    if do is not None:
+        dq = torch.full_like(q, float("nan")); dk = torch.full_like(q, float("nan")); dv = torch.full_like(q, float("nan"))
+        spa2.spa2_bwd_delta(o, do, ws_b, o_res)
+        spa2.spa2_bwd_dkdv(q, k, v, do, lse, pat, scale, dk, dv, ws_b)
+        spa2.spa2_bwd_dq(q, k, v, do, lse, pat, scale, dq, ws_b)
     torch.cuda.synchronize()
     return k_cnt, pat, pbar, o, lse, dq, dk, dv
 
 
+OVER_PLAIN = {}     # (workload, tensor) -> [elements compared, elements whose error exceeds the plain 2e-2]
+
+
+def _tally(wname, tensor, got, ref, **bars):
+    e = assert_close(f"{wname} {tensor}", got, ref, **bars)
+    t = OVER_PLAIN.setdefault((wname, tensor), [0, 0, 0.0])
+    t[0] += ref.size; t[1] += int((np.abs(got - ref) > MAX_ABS).sum()); t[2] = max(t[2], e[0])
+    return e
+
+
 def _check_head_samples(w, b, h, q, k, v, do, pat, o, lse, dq, dk, dv, q_blocks, kv_blocks):
     """Oracle on one head, restricted to sampled query blocks (O, LSE, dQ rows) and to the query
-    blocks that selected the sampled key blocks (dK, dV rows), using the GPU's own mask."""
+    blocks that selected the sampled key blocks (dK, dV rows), using the GPU's own mask.
+    Bars: max(2e-2, 2^-7 x row max) and max(2e-3, 2^-8 x mean|ref|) for every tensor, i.e. the plain 2e-2 / 2e-3
+    wherever a row's values stay below 2.56; dQ on the low-rank workloads gets a 5e-2 floor instead of 2e-2.  Both
+    widenings are derived on the CPU in tests/test_tolerance_model.py."""
     mask = pat.mask[b, h].cpu().numpy()
-    qh, kh, vh, doh = (f64(t[b, h]) for t in (q, k, v, do))
-    r_dq, _, _, r_o, r_lse = orc.attention_bwd_gather(qh, kh, vh, mask, doh, q_blocks=q_blocks)
+    lowrank = w.kind == "lowrank"
+    qh, kh, vh = (f64(t[b, h]) for t in (q, k, v))
+    if do is None:
+        r_o, r_lse = orc.attention_gather(qh, kh, vh, mask, q_blocks=q_blocks)
+    else:
+        doh = f64(do[b, h])
+        r_dq, _, _, r_o, r_lse = orc.attention_bwd_gather(qh, kh, vh, mask, doh, q_blocks=q_blocks)
     for i in q_blocks:
         r0, r1 = i * 128, min(w.N, (i + 1) * 128)
-        assert_close(f"O[{b},{h}] block {i}", f64(o[b, h, r0:r1]), r_o[r0:r1])
-        # dQ sums bf16-rounded dS (2^-9 relative) against keys of magnitude ~10 (the scale-2 low-rank part of
-        # these workloads): single elements reach 3.3e-2 even in an otherwise exact numpy emulation of that
-        # one rounding, which the GPU reproduces to 5e-3.  The plain 2e-2 bar is kept for O and dV and for
-        # every small configuration; here dQ gets 5e-2 max-abs, the mean bar is unchanged.
-        e = assert_close(f"dQ[{b},{h}] block {i}", f64(dq[b, h, r0:r1]), r_dq[r0:r1], max_abs=5e-2)
-        print(f"  q block {i}: dQ max/mean err, elements above 2e-2: {e[0]:.4f} {e[1]:.5f} "
-              f"{int((np.abs(f64(dq[b, h, r0:r1]) - r_dq[r0:r1]) > 2e-2).sum())}", flush=True)
+        _tally(w.name, "O", f64(o[b, h, r0:r1]), r_o[r0:r1])
         assert np.abs(f64(lse[b, h, r0:r1]) - r_lse[r0:r1]).max() <= 2e-3
+        if do is not None:
+            e = _tally(w.name, "dQ", f64(dq[b, h, r0:r1]), r_dq[r0:r1], max_abs=LOWRANK_MAX_ABS if lowrank else MAX_ABS)
+            print(f"  ({b},{h}) q block {i} ({int(mask[i].sum())} tiles): dQ max/mean err {e[0]:.4f} {e[1]:.5f}, "
+                  f"elements above 2e-2: {int((np.abs(f64(dq[b, h, r0:r1]) - r_dq[r0:r1]) > MAX_ABS).sum())}", flush=True)
+    if do is None:
+        return
     for j in kv_blocks:
         rows = [int(i) for i in np.flatnonzero(mask[:, j])]
         _, r_dk, r_dv, _, _ = orc.attention_bwd_gather(qh, kh, vh, mask, doh, q_blocks=rows)
         c0, c1 = j * 64, min(w.N, (j + 1) * 64)
-        e = assert_close(f"dK[{b},{h}] block {j} ({len(rows)} query blocks)", f64(dk[b, h, c0:c1]), r_dk[c0:c1])
-        assert_close(f"dV[{b},{h}] block {j}", f64(dv[b, h, c0:c1]), r_dv[c0:c1])
-        print(f"  kv block {j}: {len(rows)} query blocks, dK max/mean err {e}", flush=True)
+        e = _tally(w.name, "dK", f64(dk[b, h, c0:c1]), r_dk[c0:c1])
+        _tally(w.name, "dV", f64(dv[b, h, c0:c1]), r_dv[c0:c1])
+        print(f"  ({b},{h}) kv block {j}: {len(rows)} query blocks, max|dK ref| {np.abs(r_dk[c0:c1]).max():.1f}, "
+              f"dK max/mean err, above 2e-2: {e[0]:.4f} {e[1]:.5f} {e[2]}", flush=True)
+
+
+def _print_tally(wname):
+    for (wn, tensor), (n, over, worst) in sorted(OVER_PLAIN.items()):
+        if wn == wname:
+            print(f"  {wname} {tensor}: {over} of {n} compared elements above the plain 2e-2 (worst {worst:.4f})", flush=True)
+
+
+def _mask_protocol_all_heads(w, q, k, pat, pbar, k_cnt, top_p):
+    """Alg. 1 steps 4-6 against the oracle on EVERY head: scores, selection rule on the exported scores, distance
+    to the all-fp64 mask.  Returns the summed flip counts."""
+    tot = {}
+    for b in range(w.B):
+        for h in range(w.H):
+            ref_pbar = orc.pooled_map(f64(q[b, h]), f64(k[b, h]))
+            r = mask_protocol(pat.mask[b, h].cpu().numpy(), pbar[b, h].cpu().numpy(), ref_pbar, k_cnt, top_p)
+            assert r["stage1_max_rel"] <= 1e-5 and r["stage2_unexplained"] == 0 and r["stage3_unexplained"] == 0, (b, h, r)
+            tot["stage1_max_rel"] = max(tot.get("stage1_max_rel", 0.0), r["stage1_max_rel"])
+            for key, val in r.items():
+                if key != "stage1_max_rel":
+                    tot[key] = tot.get(key, 0) + val
+    return tot
 
 
 def _properties(w, pat, o, lse, dq, dk, dv, k_cnt):
     """Hold at any size: every output finite and fully written, pattern encodings agree in
     aggregate, every row keeps at least max(1, k_cnt) blocks."""
     for name, t in (("O", o), ("dQ", dq), ("dK", dk), ("dV", dv), ("LSE", lse)):
-        assert torch.isfinite(t).all(), name
+        assert t is None or torch.isfinite(t).all(), name
     m = pat.mask
     assert int(m.max()) <= 1
     assert torch.equal(pat.row_cnt.long(), m.sum(-1, dtype=torch.int64))
@@ -87,27 +129,27 @@ def _properties(w, pat, o, lse, dq, dk, dv, k_cnt):
         assert torch.equal(pat.row_idx[b, h, i, :c].long(), torch.nonzero(m[b, h, i]).flatten())
 
 
-@pytest.mark.parametrize("w", [wl.WAN13_95, wl.WAN14_95], ids=lambda w: w.name)
+@pytest.mark.parametrize("w", [wl.WAN13_FWD, wl.WAN13_95, wl.WAN14_95], ids=lambda w: w.name)
 def test_wan_like_layers_sampled(w):
-    print(f"workload {w.name}: B={w.B} H={w.H} N={w.N} d={w.d}", flush=True)
+    print(f"workload {w.name}: B={w.B} H={w.H} N={w.N} d={w.d} k={w.k_frac} p={w.top_p} backward={w.backward}", flush=True)
     q, k, v, do = wl.make_inputs(w, seed=0, device=dev())
     k_cnt, pat, pbar, o, lse, dq, dk, dv = _run_path(w, q, k, v, do)
     _properties(w, pat, o, lse, dq, dk, dv, k_cnt)
     density = float(pat.mask.float().mean())
     print(f"  block sparsity {1 - density:.4f}", flush=True)
-    assert 0.90 < 1 - density < 0.95
-    heads = [(0, 0), (0, w.H - 1)]
+    lo, hi = (0.85, 0.90) if w is wl.WAN13_FWD else (0.90, 0.95)
+    assert lo < 1 - density < hi
+    tot = _mask_protocol_all_heads(w, q, k, pat, pbar, k_cnt, w.top_p)
+    print(f"  mask protocol over all {w.B * w.H} heads: {tot}", flush=True)
+    # attention samples on four heads (first, last, two in between): first query block, a Top-p-bound (longest)
+    # row, the middle, the ragged last one; hottest, an ordinary and the ragged last key block
+    heads = sorted({(0, 0), (0, w.H // 3), (0, (2 * w.H) // 3), (0, w.H - 1)})
     for (b, h) in heads:
-        # mask protocol on the whole head
-        ref_pbar = orc.pooled_map(f64(q[b, h]), f64(k[b, h]))
-        r = mask_protocol(pat.mask[b, h].cpu().numpy(), pbar[b, h].cpu().numpy(), ref_pbar, k_cnt, w.top_p)
-        print(f"  head ({b},{h}) mask protocol: {r}", flush=True)
-        assert r["stage1_max_rel"] <= 1e-5 and r["stage2_unexplained"] == 0 and r["stage3_unexplained"] == 0
-        # sampled blocks: first, a Top-p-bound (longest) row, the ragged last ones; hottest and last key blocks
         rc = pat.row_cnt[b, h].cpu().numpy(); cc = pat.col_cnt[b, h].cpu().numpy()
         q_blocks = sorted({0, int(rc.argmax()), w.Tm // 2, w.Tm - 1})
         kv_blocks = sorted({int(cc.argmax()), w.Tn // 3, w.Tn - 1})
         _check_head_samples(w, b, h, q, k, v, do, pat, o, lse, dq, dk, dv, q_blocks, kv_blocks)
+    _print_tally(w.name)
 
 
 def test_head_dim_64_layer_sampled():
@@ -118,39 +160,40 @@ def test_head_dim_64_layer_sampled():
     q, k, v, do = wl.make_inputs(w, seed=0, device=dev())
     k_cnt, pat, pbar, o, lse, dq, dk, dv = _run_path(w, q, k, v, do)
     _properties(w, pat, o, lse, dq, dk, dv, k_cnt)
-    b, h = 1, 2
-    ref_pbar = orc.pooled_map(f64(q[b, h]), f64(k[b, h]))
-    r = mask_protocol(pat.mask[b, h].cpu().numpy(), pbar[b, h].cpu().numpy(), ref_pbar, k_cnt, w.top_p)
-    print(f"  head ({b},{h}) mask protocol: {r}", flush=True)
-    assert r["stage1_max_rel"] <= 1e-5 and r["stage2_unexplained"] == 0 and r["stage3_unexplained"] == 0
-    rc = pat.row_cnt[b, h].cpu().numpy(); cc = pat.col_cnt[b, h].cpu().numpy()
-    _check_head_samples(w, b, h, q, k, v, do, pat, o, lse, dq, dk, dv,
-                        q_blocks=sorted({0, int(rc.argmax()), w.Tm - 1}), kv_blocks=sorted({int(cc.argmax()), w.Tn - 1}))
+    print(f"  mask protocol over all heads: {_mask_protocol_all_heads(w, q, k, pat, pbar, k_cnt, w.top_p)}", flush=True)
+    for (b, h) in ((1, 2), (0, 0)):
+        rc = pat.row_cnt[b, h].cpu().numpy(); cc = pat.col_cnt[b, h].cpu().numpy()
+        _check_head_samples(w, b, h, q, k, v, do, pat, o, lse, dq, dk, dv,
+                            q_blocks=sorted({0, int(rc.argmax()), w.Tm - 1}), kv_blocks=sorted({int(cc.argmax()), w.Tn - 1}))
+    _print_tally(w.name)
 
 
 STRESS_SETTINGS = [(kf, p) for kf in (0.02, 0.05, 0.10) for p in (0.5, 0.8, 0.95)]
 
 
 def test_mask_stress_sweep():
-    """Near-uniform rows (thousands of near-ties) and sink-dominated rows: the mask must still equal
-    the oracle's selection on the exported scores; flips are counted per setting."""
+    """Near-uniform rows (thousands of near-ties) and sink-dominated rows: on every head and every setting the mask
+    must equal the oracle's selection on the exported scores; flips are counted per setting.  Attention samples on
+    four of the nine settings, two heads each."""
     w = wl.MASK_STRESS
     print(f"workload {w.name}: B={w.B} H={w.H} N={w.N} d={w.d}", flush=True)
     q, k, v, do = wl.make_inputs(w, seed=0, device=dev())
-    ref_pbar = {(b, h): orc.pooled_map(f64(q[b, h]), f64(k[b, h])) for (b, h) in [(0, 0), (1, 7)]}
+    ref_pbar = {(b, h): orc.pooled_map(f64(q[b, h]), f64(k[b, h])) for b in range(w.B) for h in range(w.H)}
     for si, (kf, p) in enumerate(STRESS_SETTINGS):
         k_cnt, pat, pbar, o, lse, dq, dk, dv = _run_path(w, q, k, v, do, kf, p)
         _properties(w, pat, o, lse, dq, dk, dv, k_cnt)
         tot = {}
+        mask_all = pat.mask.cpu().numpy(); pbar_all = pbar.cpu().numpy()
         for (b, h), rp in ref_pbar.items():
-            r = mask_protocol(pat.mask[b, h].cpu().numpy(), pbar[b, h].cpu().numpy(), rp, k_cnt, p)
+            r = mask_protocol(mask_all[b, h], pbar_all[b, h], rp, k_cnt, p)
             assert r["stage1_max_rel"] <= 1e-5 and r["stage2_unexplained"] == 0 and r["stage3_unexplained"] == 0, r
             for key, val in r.items():
                 if key.startswith("stage") and key != "stage1_max_rel":
                     tot[key] = tot.get(key, 0) + val
-        print(f"  k={kf} p={p}: k_cnt={k_cnt} density={float(pat.mask.float().mean()):.4f} flips={tot}", flush=True)
-        if si in (1, 8):      # attention spot checks on two settings (sparse-ish and dense-ish)
-            b, h = 1, 7
-            cc = pat.col_cnt[b, h].cpu().numpy()
-            _check_head_samples(w, b, h, q, k, v, do, pat, o, lse, dq, dk, dv,
-                                q_blocks=[0, 1, w.Tm - 1], kv_blocks=[0, int(cc[1:].argmax()) + 1])
+        print(f"  k={kf} p={p}: k_cnt={k_cnt} density={float(pat.mask.float().mean()):.4f} flips over {len(ref_pbar)} heads={tot}", flush=True)
+        if si in (0, 1, 5, 8):      # attention spot checks: sparsest, the default, a mixed and the densest setting
+            for (b, h) in ((1, 7), (0, 3)):
+                cc = pat.col_cnt[b, h].cpu().numpy()
+                _check_head_samples(w, b, h, q, k, v, do, pat, o, lse, dq, dk, dv,
+                                    q_blocks=[0, 1, w.Tm - 1], kv_blocks=[0, int(cc[1:].argmax()) + 1])
+    _print_tally(w.name)
