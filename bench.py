@@ -185,7 +185,10 @@ def main():
             traffic = None
     roofline = {"kernel": dom, "bound": "mfma", "achieved": kern[dom]["alg_tflops"], "peak": PEAK_BF16_TFLOPS,
                 "unit": "TFLOP/s", "frac": kern[dom]["alg_tflops"] / PEAK_BF16_TFLOPS, "traffic": traffic,
-                "ms_per_launch": kern[dom]["ms"]}
+                "ms_per_launch": kern[dom]["ms"],
+                # not measured in this run: counters need rocprofv3 around the process
+                "traffic_source": "profiles/traffic.json (rocprofv3 FETCH_SIZE + WRITE_SIZE runs of this command, see profiles/)"
+                                  if traffic is not None else None}
 
     # the same step with the two backward kernels launched at the same time on two streams (the operator's
     # overlap_backward option).  Reported beside the headline, never as it: per-kernel durations, and with them

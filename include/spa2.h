@@ -107,8 +107,14 @@ size_t spa2_bwd_workspace_bytes(const spa2_shape* shape);
  *   out         all five arrays are written (col_* may be NULL if no backward follows).
  *   pbar_out    optional fp32 [B,H,T_m,T_n]: the pooled map the selection was taken on.
  * Per row: entries are ordered by (Pbar descending, block index ascending);
- * n_p is the shortest prefix whose sum (accumulated in fp64, in that order)
- * is >= top_p; the first max(1, topk_blocks, n_p) entries are selected. */
+ * n_p is the shortest prefix whose sum is >= top_p; the first
+ * max(1, topk_blocks, n_p) entries are selected.  The prefix sums are exact
+ * integer sums of the fp32 Pbar values taken as 62-bit fixed point (each value
+ * times 2^62, bits below 2^-62 dropped; top_p converted the same way), so
+ * they do not depend on the order of addition and the mask is deterministic.
+ * Against a sequential fp64 sum of the same fp32 values the cut can differ
+ * only where the cumulative mass lies within rounding (far below 1e-5) of
+ * top_p. */
 int spa2_mask(const void* q, const void* k, const spa2_shape* shape,
               int32_t topk_blocks, float top_p, float scale,
               spa2_pattern* out, float* pbar_out,

@@ -15,7 +15,10 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 BUILD = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libspa2.so")
-SOURCES = ["api.hip", "mask.hip", "fwd.hip", "bwd.hip", "diag.hip", "distill.hip"]
+SOURCES = ["api.hip", "mask.hip", "fwd.hip", "bwd.hip", "bwd_dkdv.hip", "diag.hip", "distill.hip"]
+# per-file flags: the dK/dV kernel mixes matrix products whose results the vector ALU reads (kept in ordinary
+# registers by this option) with accumulators that it pins to the accumulation registers itself
+EXTRA = {"bwd_dkdv.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
 HIPCC = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
 FLAGS = [
@@ -31,7 +34,7 @@ FLAGS = [
 
 def _compile(src: str, extra=()) -> str:
     obj = os.path.join(BUILD, os.path.splitext(src)[0] + ".o")
-    cmd = [HIPCC, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [HIPCC, *FLAGS, *EXTRA.get(src, []), *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
     if r.returncode != 0:

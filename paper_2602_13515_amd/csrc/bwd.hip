@@ -300,322 +300,4 @@ hipError_t launch_bwd_dq(const void* q, const void* k, const void* v, const void
   return hipGetLastError();
 }
 
-// ------------------------------------------------------------------ dK, dV
-struct DkvArgs {
-  const uint16_t* q; const uint16_t* k; const uint16_t* v; const uint16_t* d_o;
-  const float* lse; const float* delta; uint16_t* dk; uint16_t* dv;
-  const int32_t* col_cnt; const int32_t* col_idx; const int32_t* col_order;
-  int H, N, Tm, Tn, chunk;
-  int64_t sb, sh, sn;
-  float scale, scale_log2;
-};
-
-// One workgroup (4 waves) per key block j (64 keys), two workgroups per CU.  The query blocks that selected
-// j are taken in halves of 64 rows.  Wave (wq, wk) owns the 32 queries 32wq.. of the current half and the 32
-// keys 32wk.. of the key block; it keeps its K^T / V^T fragments and its dK^T / dV^T accumulators (d x 32 keys
-// each) in registers for the whole kernel.  Q and dO of a half (64 x d each) are copied global -> LDS directly
-// (no register staging), XOR-swizzled so that both read patterns are conflict-free, double-buffered one half
-// ahead:
-//   S  (q x keys) = Q_i K_j^T        A = Q rows from LDS,  B = K^T fragments (registers)
-//   dP (q x keys) = dO_i V_j^T       A = dO rows from LDS, B = V^T fragments (registers)
-//   P = exp(S - LSE), dS = P * (dP - D)      accumulator layout: lane = key, registers = queries
-//   dV^T (d x keys) += dO_i^T P      A = dO^T through transposing LDS reads, B = P  (registers)
-//   dK^T (d x keys) += Q_i^T dS      A = Q^T  through transposing LDS reads, B = dS (registers)
-// Every MFMA (32x32x16) has exactly one operand from LDS.  The two waves that share a key half add their
-// partial sums through LDS at the end.  (Half tiles keep a stage at 32 KB, so that two workgroups fit a CU
-// and fill each other's barrier and copy waits; with whole tiles and eight waves only one does.)
-template <int D>
-__global__ __launch_bounds__(256, 2) void dkdv_kernel(DkvArgs a) {
-  constexpr int HQ = 64;                             // query rows per step
-  constexpr int HALF = HQ * D;                       // elements of one 64-row half tile
-  constexpr int CPR = D / 8;                         // 16-byte chunks per row
-  constexpr int RP = 256 / CPR;                      // rows covered by one copy instruction of the workgroup
-  constexpr int CH = HQ / RP;                        // copy instructions per thread per half tile and tensor
-  __shared__ __align__(16) uint16_t smem[4 * HALF];  // stage s: Q half at 2s*HALF, dO half at (2s+1)*HALF
-  __shared__ __align__(16) float lse_s[2 * HQ];
-  __shared__ __align__(16) float dlt_s[2 * HQ];
-
-  const HeadBlock hbk = xcd_map(blockIdx.x, a.Tn, a.chunk);
-  if (!hbk.valid) return;
-  const int bh = hbk.bh;
-  const int j = a.col_order ? min(max(a.col_order[(int64_t)bh * a.Tn + hbk.blk], 0), a.Tn - 1) : hbk.blk;
-  const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int wq = w & 1, wk = w >> 1;
-  const int r32 = lane & 31, hf = lane >> 5;
-  const int N = a.N;
-  const int cnt = min(max(a.col_cnt[(int64_t)bh * a.Tn + j], 0), a.Tm);   // clamped: see fwd.hip
-  const int32_t* idx = a.col_idx + ((int64_t)bh * a.Tn + j) * a.Tm;
-
-  const int key = j * BKV + wk * 32 + r32;
-  const bool key_ok = key < N;
-
-  if (cnt == 0) {   // no query block selected this key block: zero gradients
-    if (key_ok && wq == 0) {
-      const int64_t out_off = base + (int64_t)key * a.sn + 4 * hf;
-#pragma unroll
-      for (int c = 0; c < D / 8; ++c) {
-        *(u32x2*)(a.dk + out_off + 8 * c) = u32x2{0, 0};
-        *(u32x2*)(a.dv + out_off + 8 * c) = u32x2{0, 0};
-      }
-    }
-    return;
-  }
-
-  // K^T / V^T fragments (B operands): lane = key, 8 consecutive channels per 16-wide k step
-  bf16x8 kf[D / 16], vf[D / 16];
-  {
-    const int64_t off = base + (int64_t)(key_ok ? key : N - 1) * a.sn + 8 * hf;
-#pragma unroll
-    for (int kk = 0; kk < D / 16; ++kk) {
-      kf[kk] = *(const bf16x8*)(a.k + off + 16 * kk);
-      vf[kk] = *(const bf16x8*)(a.v + off + 16 * kk);
-    }
-  }
-
-  f32x16 dk_acc[D / 32], dv_acc[D / 32];
-#pragma unroll
-  for (int mb = 0; mb < D / 32; ++mb)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) { dk_acc[mb][v] = 0.f; dv_acc[mb][v] = 0.f; }
-
-  // global -> LDS copy of one half tile.  The destination of a wave-wide 16-byte-per-lane copy is
-  // linear (wave base + 16 * lane), so the swizzle is applied on the source side: the lane that fills
-  // chunk position pc of row `row` fetches logical chunk pc ^ swz(row).  Rows past N are clamped to the
-  // last token and get LSE = +inf, so their P and dS are exactly zero.
-  // thread t fills chunk position t % CPR of rows t / CPR + r * RP; RP is a multiple of 16 rows, so the
-  // swizzle term is the same for every r
-  float stat = 0.f;                                    // LSE (wave 0) or D (wave 1) of one row
-  // Everything a request needs is either wave-uniform (scalar registers) or one 32-bit lane offset:
-  // the loop body then issues the copies without vector address arithmetic and without waiting on
-  // anything (a wait on any vector-memory result would also wait for the copies queued before it).
-  const int ld_row0 = tid / CPR;
-  const int ld_c8 = ((tid % CPR) ^ swz<D>(ld_row0)) * 8;
-  const uint32_t goff = (uint32_t)((ld_row0 * a.sn + ld_c8) * 2);                        // bytes, r = 0
-  const uint64_t row_step = (uint64_t)RP * (uint64_t)a.sn * 2;                              // bytes per r
-  const char* q_head = (const char*)(a.q + base);
-  const char* o_head = (const char*)(a.d_o + base);
-  // (a pointer in the global address space: through a generic one the load below could alias LDS and
-  // would have to wait for the copies queued before it)
-  typedef const __attribute__((address_space(1))) float* gfloat_ptr;
-  gfloat_ptr stat_src;
-  {
-    const uint64_t sp = (uint64_t)((w == 0 ? a.lse : a.delta) + (int64_t)bh * N);
-    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)sp), hi = __builtin_amdgcn_readfirstlane((uint32_t)(sp >> 32));
-    stat_src = (gfloat_ptr)(((uint64_t)hi << 32) | lo);
-  }
-  // the index list, 64 entries at a time in one register (lane l holds entry 64c + l): reading entry t is a
-  // lane read, not a memory access
-  int idx_v = idx[min(lane, cnt - 1)];
-  auto list_entry = [&](int t) -> int {      // t uniform, inside the chunk that idx_v holds
-    return min(max(__builtin_amdgcn_readlane(idx_v, t & 63), 0), a.Tm - 1);
-  };
-  // One request = 2 * CH copy instructions per lane.  The texture unit takes them at about one
-  // 16-byte lane group per few cycles, and a wave that issues them back to back sits at the issue
-  // stage until the last one is accepted; so for a full half tile they are handed out one at a time
-  // between the MFMAs of the S / dP loop (request_piece), and only a half that reaches past N is
-  // requested in one go (request_ragged).  row0 is the first token of the half.
-  auto request_stat = [&](int row0) {
-    if (w < 2) {
-      const int srow = row0 + lane;
-      // (the conversion of LSE to log2 units is left to publish_stat: using the value here would make
-      // the wave wait for every copy requested before it)
-      if (srow < N) stat = stat_src[srow];
-      else          stat = w == 0 ? INFINITY : 0.f;
-    }
-  };
-  auto request_piece = [&](int row0, int stage, int piece) {    // piece in [0, 2 CH): Q chunk, dO chunk, ...
-    const uint64_t tile_bytes = (uint64_t)row0 * (uint64_t)a.sn * 2;         // uniform
-    const int r = piece >> 1;
-    // the lane offset is made opaque here so that no per-piece 64-bit address is formed outside the loop
-    // (eight of them would be spilled): the copy then takes a scalar base plus this one 32-bit register
-    uint32_t g = goff;
-    asm volatile("" : "+v"(g));
-    const char* src = ((piece & 1) ? o_head : q_head) + tile_bytes + r * row_step + g;
-    uint16_t* dst = smem + 2 * stage * HALF + (piece & 1) * HALF + (r * 256 + w * 64) * 8;   // wave-uniform
-    __builtin_amdgcn_global_load_lds((gptr_t*)src, (lptr_t*)dst, 16, 0, 0);
-  };
-  auto request_ragged = [&](int row0, int stage) {   // rows past N are clamped to the last token
-    uint16_t* dst0 = smem + 2 * stage * HALF + w * 64 * 8;
-#pragma unroll
-    for (int r = 0; r < CH; ++r) {
-      const int64_t o2 = ((int64_t)min(row0 + ld_row0 + r * RP, N - 1) * a.sn + ld_c8) * 2;
-      uint16_t* dst = dst0 + r * 256 * 8;
-      __builtin_amdgcn_global_load_lds((gptr_t*)(q_head + o2), (lptr_t*)dst, 16, 0, 0);
-      __builtin_amdgcn_global_load_lds((gptr_t*)(o_head + o2), (lptr_t*)(dst + HALF), 16, 0, 0);
-    }
-  };
-  auto request_all = [&](int row0, int stage) {     // everything at once (prologue)
-    if (row0 + HQ <= N) {
-#pragma unroll
-      for (int piece = 0; piece < 2 * CH; ++piece) request_piece(row0, stage, piece);
-    } else {
-      request_ragged(row0, stage);
-    }
-    request_stat(row0);
-  };
-  auto publish_stat = [&](int stage) {
-    if (w == 0) lse_s[stage * HQ + lane] = stat * LOG2E;
-    else if (w == 1) dlt_s[stage * HQ + lane] = stat;
-  };
-
-  // per-lane LDS element offsets inside a half tile.  Row reads: row 32wq + r32, logical chunk 2kk + hf;
-  // the chunk field of the element index is XORed with the compile-time part (kk << 4).
-  int a_base = swz_idx<D>(wq * 32 + r32, 8 * hf);
-  // transposing reads: row 32wq + 16c + 8*which + 4hf + (s16>>2), columns 32mb + 16hb + 4(s16&3);
-  // the part that depends on mb is XORed in (mb << 5)
-  const int s16 = lane & 15, hb16 = (lane >> 4) & 1;
-  int t_base0 = swz_idx<D>(wq * 32 + 4 * hf + (s16 >> 2), 16 * hb16 + 4 * (s16 & 3));
-  int t_base1 = swz_idx<D>(wq * 32 + 8 + 4 * hf + (s16 >> 2), 16 * hb16 + 4 * (s16 & 3));
-
-  const int steps = 2 * cnt;                 // step u: half u & 1 of list entry u >> 1
-  request_all(list_entry(0) * BQ, 0);
-  publish_stat(0);
-  __syncthreads();
-
-  for (int u = 0; u < steps; ++u) {
-    const bool more = u + 1 < steps;
-    int row_nx = 0;
-    bool piecewise = false;
-    if (more) {
-      if (((u + 1) & 127) == 0) idx_v = idx[min(((u + 1) >> 1) + lane, cnt - 1)];   // next 64 entries of the list
-      row_nx = list_entry((u + 1) >> 1) * BQ + ((u + 1) & 1) * HQ;
-      piecewise = row_nx + HQ <= N;
-      if (!piecewise) request_ragged(row_nx, (u + 1) & 1);
-      request_stat(row_nx);
-    }
-    const int st = u & 1;
-    const uint16_t* Qb = smem + 2 * st * HALF;
-    const uint16_t* Ob = Qb + HALF;
-    const float* lb = lse_s + st * HQ + wq * 32;
-    const float* db = dlt_s + st * HQ + wq * 32;
-    // keep the XORed operand addresses out of loop-invariant hoisting: recomputing them costs one
-    // VALU op per read, keeping sixteen of them live costs registers this kernel does not have
-    asm volatile("" : "+v"(a_base), "+v"(t_base0), "+v"(t_base1));
-
-    // --- S and dP: LDS operands are requested two MFMA pairs ahead of their use
-    f32x16 s, dp;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) { s[v] = 0.f; dp[v] = 0.f; }
-    {
-      bf16x8 fq[2], fo[2];
-#pragma unroll
-      for (int x = 0; x < 2; ++x) {
-        fq[x] = *(const bf16x8*)(Qb + (a_base ^ (x << 4)));
-        fo[x] = *(const bf16x8*)(Ob + (a_base ^ (x << 4)));
-      }
-#pragma unroll
-      for (int kk = 0; kk < D / 16; ++kk) {
-        s = mfma32(fq[kk & 1], kf[kk], s);
-        if (kk + 2 < D / 16) fq[kk & 1] = *(const bf16x8*)(Qb + (a_base ^ ((kk + 2) << 4)));
-        dp = mfma32(fo[kk & 1], vf[kk], dp);
-        if (kk + 2 < D / 16) fo[kk & 1] = *(const bf16x8*)(Ob + (a_base ^ ((kk + 2) << 4)));
-        // the 2 CH copies of the next half, one per step
-        if (piecewise) {
-#pragma unroll
-          for (int c = 0; c < (2 * CH) / (D / 16); ++c) request_piece(row_nx, (u + 1) & 1, kk * ((2 * CH) / (D / 16)) + c);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    }
-    // --- P and dS.  Accumulator register v holds query 8*(v/4) + 4hf + v%4 of this wave's 32 queries.
-    uint32_t pk[8], dsk[8];
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      const f32x4 l4 = *(const f32x4*)(lb + 8 * g + 4 * hf);
-      const f32x4 d4 = *(const f32x4*)(db + 8 * g + 4 * hf);
-      float p[4], ds[4];
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        p[e] = fast_exp2(fmaf(s[4 * g + e], a.scale_log2, -l4[e]));
-        if (!key_ok) p[e] = 0.f;
-        ds[e] = p[e] * (dp[4 * g + e] - d4[e]);
-      }
-      pk[2 * g] = pack_bf16(p[0], p[1]);    pk[2 * g + 1] = pack_bf16(p[2], p[3]);
-      dsk[2 * g] = pack_bf16(ds[0], ds[1]); dsk[2 * g + 1] = pack_bf16(ds[2], ds[3]);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    // --- dV^T and dK^T.  MFMA pair x = (c, mb): 16 queries per MFMA (slots 16c + 4hf + {0..3} and + 8),
-    // output block mb; transposed operands requested PDT pairs ahead.
-    {
-      constexpr int NX = 2 * (D / 32), PDT = 2;
-      auto tr_frag = [&](const uint16_t* tile, int x) {
-        const int c = x / (D / 32), mb = x % (D / 32);
-        return join_tr(lds_read_tr4(tile + (t_base0 ^ (mb << 5)) + 16 * c * D),
-                       lds_read_tr4(tile + (t_base1 ^ (mb << 5)) + 16 * c * D));
-      };
-      bf16x8 fo[PDT], fq[PDT];
-#pragma unroll
-      for (int x = 0; x < PDT; ++x) { fo[x] = tr_frag(Ob, x); fq[x] = tr_frag(Qb, x); }
-#pragma unroll
-      for (int x = 0; x < NX; ++x) {
-        const int c = x / (D / 32), mb = x % (D / 32);
-        const u32x4 pu = {pk[4 * c], pk[4 * c + 1], pk[4 * c + 2], pk[4 * c + 3]};
-        const u32x4 du = {dsk[4 * c], dsk[4 * c + 1], dsk[4 * c + 2], dsk[4 * c + 3]};
-        dv_acc[mb] = mfma32(fo[x % PDT], __builtin_bit_cast(bf16x8, pu), dv_acc[mb]);
-        if (x + PDT < NX) fo[x % PDT] = tr_frag(Ob, x + PDT);
-        dk_acc[mb] = mfma32(fq[x % PDT], __builtin_bit_cast(bf16x8, du), dk_acc[mb]);
-        if (x + PDT < NX) fq[x % PDT] = tr_frag(Qb, x + PDT);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    }
-    if (more) publish_stat((u + 1) & 1);
-    __syncthreads();      // also waits for the global -> LDS copies requested in this step
-  }
-
-  // sum the partial results of the two query groups of each key half: first pass dK, second pass dV.
-  // Wave (wq, wk) finishes the output blocks mb = wq * NMB .. + NMB - 1 of its key half.
-  float* scratch = (float*)smem;
-  constexpr int REGION = (D / 32) * 16 * 64;          // floats per wave
-  constexpr int NMB = (D / 32) / 2;                   // output blocks per finishing wave
-  static_assert(4 * REGION * 4 <= 4 * HALF * 2, "the reduction scratch reuses the tile stages");
-#pragma unroll
-  for (int round = 0; round < 2; ++round) {
-    float* mine = scratch + w * REGION + lane;
-#pragma unroll
-    for (int mb = 0; mb < D / 32; ++mb)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) mine[(mb * 16 + v) * 64] = round == 0 ? dk_acc[mb][v] : dv_acc[mb][v];
-    __syncthreads();
-    if (key_ok) {
-      const int64_t out_off = base + (int64_t)key * a.sn + 4 * hf;
-      const float sc = round == 0 ? a.scale : 1.f;
-#pragma unroll
-      for (int m2 = 0; m2 < NMB; ++m2) {
-        const int mb = wq * NMB + m2;
-        uint16_t* out = (round == 0 ? a.dk : a.dv) + out_off + 32 * mb;
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          float x[4];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int v = 4 * g + e;
-            x[e] = (scratch[(wk * 2 + 0) * REGION + (mb * 16 + v) * 64 + lane] +
-                    scratch[(wk * 2 + 1) * REGION + (mb * 16 + v) * 64 + lane]) * sc;
-          }
-          u32x2 pk2 = {pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3])};
-          *(u32x2*)(out + 8 * g) = pk2;
-        }
-      }
-    }
-    __syncthreads();
-  }
-}
-
-hipError_t launch_bwd_dkdv(const void* q, const void* k, const void* v, const void* d_o, const float* lse,
-                           const float* delta, const Dims& m, const int32_t* col_cnt, const int32_t* col_idx,
-                           const int32_t* col_order, float scale, void* dk, void* dv, hipStream_t stream) {
-  DkvArgs a;
-  a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v; a.d_o = (const uint16_t*)d_o;
-  a.lse = lse; a.delta = delta; a.dk = (uint16_t*)dk; a.dv = (uint16_t*)dv;
-  a.col_cnt = col_cnt; a.col_idx = col_idx; a.col_order = col_order;
-  a.H = m.H; a.N = m.N; a.Tm = m.Tm; a.Tn = m.Tn; a.chunk = (m.Tn + 7) / 8;
-  a.sb = m.sb; a.sh = m.sh; a.sn = m.sn;
-  a.scale = scale; a.scale_log2 = scale * LOG2E;
-  const dim3 grid((unsigned)(m.B * m.H * 8 * a.chunk)), block(256);
-  if (m.d == 128) hipLaunchKernelGGL(dkdv_kernel<128>, grid, block, 0, stream, a);
-  else            hipLaunchKernelGGL(dkdv_kernel<64>, grid, block, 0, stream, a);
-  return hipGetLastError();
-}
-
 }  // namespace spa2

@@ -95,6 +95,41 @@ __device__ __forceinline__ void raw_copies_done() {
 #endif
 }
 
+// LDS accesses by 32-bit byte address.  A generic pointer into LDS is turned into its LDS address once
+// (lds_addr_of); from then on addresses are plain integers, so that address arithmetic stays 32-bit and constant
+// parts can be folded into the instructions' offset fields, and no generic-pointer null checks are generated.
+typedef __attribute__((address_space(3))) const bf16x8 lds_cbf16x8;
+typedef __attribute__((address_space(3))) const f32x4 lds_cf32x4;
+__device__ __forceinline__ uint32_t lds_addr_of(const void* p) { return (uint32_t)(size_t)(lptr_t*)p; }
+#if defined(__HIP_DEVICE_COMPILE__)      // (LDS pointers are 32 bits wide only in the device pass)
+__device__ __forceinline__ bf16x8 lds_ld16(uint32_t addr) { return *(lds_cbf16x8*)addr; }
+__device__ __forceinline__ f32x4 lds_ldf4(uint32_t addr) { return *(lds_cf32x4*)addr; }
+__device__ __forceinline__ u32x2 lds_tr4_at(uint32_t addr) {
+  s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)addr);
+  return __builtin_bit_cast(u32x2, v);
+}
+#else
+__device__ bf16x8 lds_ld16(uint32_t addr);
+__device__ f32x4 lds_ldf4(uint32_t addr);
+__device__ u32x2 lds_tr4_at(uint32_t addr);
+#endif
+// Direct global -> LDS copies as above, with the (wave-uniform) LDS byte address given as an integer.
+// LDS_CONST is a compile-time part of the destination that is added while m0 is written.
+template <int LDS_CONST>
+__device__ __forceinline__ void raw_copy16_to_lds_at(const void* src_base, uint32_t src_off, uint32_t lds_addr) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  asm volatile("s_add_u32 m0, %0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :: "s"(lds_addr), "v"(src_off), "s"(src_base), "n"(LDS_CONST) : "memory", "m0", "scc");
+#endif
+}
+template <int LDS_CONST>
+__device__ __forceinline__ void raw_copy4_to_lds_at(const void* src_base, uint32_t src_off, uint32_t lds_addr) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  asm volatile("s_add_u32 m0, %0, %3\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
+               :: "s"(lds_addr), "v"(src_off), "s"(src_base), "n"(LDS_CONST) : "memory", "m0", "scc");
+#endif
+}
+
 // XOR-swizzled LDS tile: rows of D bf16, unpadded; the 16-byte chunk c of row r lives at chunk position
 // c ^ swz<D>(r).  The function is chosen so that BOTH access patterns the kernels use are free of bank
 // conflicts (64 banks x 4 bytes): 16 lanes reading the same chunk of 16 consecutive rows (MFMA operand read

@@ -22,6 +22,45 @@ def dev():
     return torch.device("cuda:0")
 
 
+# ---- canaries: every output buffer of a call sits between two guard zones holding a sentinel pattern; after the
+# call the zones must be untouched (an out-of-bounds write next to a buffer shows here, a NaN fill only shows
+# elements that were never written)
+GUARD_BYTES = 4096
+_SENTINEL = 0xA5
+
+
+class Guarded:
+    def __init__(self):
+        self.items = []
+
+    def alloc(self, shape, dtype, device, fill):
+        n = int(np.prod(shape))
+        esz = torch.empty((), dtype=dtype).element_size()
+        raw = torch.full((n * esz + 2 * GUARD_BYTES,), _SENTINEL, dtype=torch.uint8, device=device)
+        body = raw[GUARD_BYTES:GUARD_BYTES + n * esz].view(dtype).view(shape)
+        body.fill_(fill)
+        self.items.append((raw, n * esz))
+        return body
+
+    def check(self, where=""):
+        for raw, nbytes in self.items:
+            lo, hi = raw[:GUARD_BYTES], raw[GUARD_BYTES + nbytes:]
+            assert bool((lo == _SENTINEL).all()) and bool((hi == _SENTINEL).all()), \
+                f"{where}: a kernel wrote outside an output buffer of {nbytes} bytes"
+
+
+def guarded_pattern(g: Guarded, B, H, N, device, columns=True):
+    Tm, Tn = -(-N // 128), -(-N // 64)
+    i32 = torch.int32
+    return spa2.Pattern(
+        mask=g.alloc((B, H, Tm, Tn), torch.uint8, device, 7),
+        row_cnt=g.alloc((B, H, Tm), i32, device, -1),
+        row_idx=g.alloc((B, H, Tm, Tn), i32, device, -1),
+        col_cnt=g.alloc((B, H, Tn), i32, device, -1) if columns else None,
+        col_idx=g.alloc((B, H, Tn, Tm), i32, device, -1) if columns else None,
+        col_order=g.alloc((B, H, Tn), i32, device, -1) if columns else None)
+
+
 def f64(t: torch.Tensor) -> np.ndarray:
     return t.detach().to("cpu").double().numpy()
 
@@ -49,37 +88,39 @@ def pattern_from_mask(mask: np.ndarray, device) -> spa2.Pattern:
 def gpu_mask(q, k, k_cnt, top_p, scale=None, want_pbar=True, columns=True):
     B, H, N, d = q.shape
     scale = 1.0 / math.sqrt(d) if scale is None else scale
-    pat = spa2.alloc_pattern(B, H, N, q.device, columns=columns)
-    # poison the outputs so that unwritten entries show
-    pat.mask.fill_(7); pat.row_cnt.fill_(-1); pat.row_idx.fill_(-1)
-    if columns:
-        pat.col_cnt.fill_(-1); pat.col_idx.fill_(-1)
+    g = Guarded()
+    pat = guarded_pattern(g, B, H, N, q.device, columns)     # poisoned, so that unwritten entries show
     Tm, Tn = pat.mask.shape[2:]
-    pbar = torch.full((B, H, Tm, Tn), float("nan"), dtype=torch.float32, device=q.device) if want_pbar else None
-    ws = torch.empty(spa2.spa2_mask_workspace_bytes(q), dtype=torch.uint8, device=q.device)
+    pbar = g.alloc((B, H, Tm, Tn), torch.float32, q.device, float("nan")) if want_pbar else None
+    ws = g.alloc((spa2.spa2_mask_workspace_bytes(q),), torch.uint8, q.device, 0)
     spa2.spa2_mask(q, k, k_cnt, top_p, scale, pat, pbar, ws)
     torch.cuda.synchronize()
+    g.check("spa2_mask")
     return pat, pbar
 
 
 def gpu_fwd(q, k, v, pat, scale=None, residual=False):
     B, H, N, d = q.shape
     scale = 1.0 / math.sqrt(d) if scale is None else scale
-    o = torch.full_like(q, float("nan"))
-    o_res = torch.full_like(q, float("nan")) if residual else None
-    lse = torch.full((B, H, N), float("nan"), dtype=torch.float32, device=q.device)
+    g = Guarded()
+    o = g.alloc(q.shape, q.dtype, q.device, float("nan"))
+    o_res = g.alloc(q.shape, q.dtype, q.device, float("nan")) if residual else None
+    lse = g.alloc((B, H, N), torch.float32, q.device, float("nan"))
     spa2.spa2_fwd(q, k, v, pat, scale, o, lse, o_res)
     torch.cuda.synchronize()
+    g.check("spa2_fwd")
     return (o, lse, o_res) if residual else (o, lse)
 
 
 def gpu_bwd(q, k, v, o, do, lse, pat, scale=None, o_res=None):
     d = q.shape[-1]
     scale = 1.0 / math.sqrt(d) if scale is None else scale
-    dq = torch.full_like(q, float("nan")); dk = torch.full_like(q, float("nan")); dv = torch.full_like(q, float("nan"))
-    ws = torch.empty(spa2.spa2_bwd_workspace_bytes(q), dtype=torch.uint8, device=q.device)
+    g = Guarded()
+    dq, dk, dv = (g.alloc(q.shape, q.dtype, q.device, float("nan")) for _ in range(3))
+    ws = g.alloc((spa2.spa2_bwd_workspace_bytes(q),), torch.uint8, q.device, 0)
     spa2.spa2_bwd(q, k, v, o, do, lse, pat, scale, dq, dk, dv, ws, o_res)
     torch.cuda.synchronize()
+    g.check("spa2_bwd")
     return dq, dk, dv
 
 

@@ -11,7 +11,8 @@ import paper_2602_13515_amd as spa2
 from oracle import spa2_oracle as orc
 from paper_2602_13515_amd import workloads as wl
 
-from gpu_util import LOWRANK_MAX_ABS, MAX_ABS, MEAN_ABS, assert_close, dev, f64, mask_protocol
+from gpu_util import (LOWRANK_MAX_ABS, MAX_ABS, MEAN_ABS, Guarded, assert_close, dev, f64, guarded_pattern,
+                      mask_protocol)
 
 pytestmark = pytest.mark.gpu
 
@@ -22,23 +23,26 @@ def _run_path(w, q, k, v, do, k_frac=None, top_p=None, want_pbar=True):
     top_p = w.top_p if top_p is None else top_p
     scale = 1.0 / math.sqrt(w.d)
     k_cnt = spa2.spa2_topk_blocks(k_frac, w.Tn)
-    pat = spa2.alloc_pattern(w.B, w.H, w.N, q.device)
-    pbar = torch.empty((w.B, w.H, w.Tm, w.Tn), dtype=torch.float32, device=q.device) if want_pbar else None
-    ws_m = torch.empty(spa2.spa2_mask_workspace_bytes(q), dtype=torch.uint8, device=q.device)
-    ws_b = torch.empty(spa2.spa2_bwd_workspace_bytes(q), dtype=torch.uint8, device=q.device)
-    o = torch.full_like(q, float("nan")); lse = torch.empty((w.B, w.H, w.N), dtype=torch.float32, device=q.device)
-    o_res = torch.full_like(q, float("nan"))
+    g = Guarded()                      # every output between guard zones, checked after the last kernel
+    nan = float("nan")
+    pat = guarded_pattern(g, w.B, w.H, w.N, q.device)
+    pbar = g.alloc((w.B, w.H, w.Tm, w.Tn), torch.float32, q.device, nan) if want_pbar else None
+    ws_m = g.alloc((spa2.spa2_mask_workspace_bytes(q),), torch.uint8, q.device, 0)
+    ws_b = g.alloc((spa2.spa2_bwd_workspace_bytes(q),), torch.uint8, q.device, 0)
+    o = g.alloc(q.shape, q.dtype, q.device, nan); lse = g.alloc((w.B, w.H, w.N), torch.float32, q.device, nan)
+    o_res = g.alloc(q.shape, q.dtype, q.device, nan)
     spa2.spa2_mask_pool(q, k, ws_m)
     spa2.spa2_mask_select(q, k_cnt, top_p, scale, pat, pbar, ws_m)
     spa2.spa2_mask_columns(q, pat)
     spa2.spa2_fwd(q, k, v, pat, scale, o, lse, o_res)
     dq = dk = dv = None
     if do is not None:
-        dq = torch.full_like(q, float("nan")); dk = torch.full_like(q, float("nan")); dv = torch.full_like(q, float("nan"))
+        dq, dk, dv = (g.alloc(q.shape, q.dtype, q.device, nan) for _ in range(3))
         spa2.spa2_bwd_delta(o, do, ws_b, o_res)
         spa2.spa2_bwd_dkdv(q, k, v, do, lse, pat, scale, dk, dv, ws_b)
         spa2.spa2_bwd_dq(q, k, v, do, lse, pat, scale, dq, ws_b)
     torch.cuda.synchronize()
+    g.check(f"{w.name} mask / fwd / bwd")
     return k_cnt, pat, pbar, o, lse, dq, dk, dv
 
 
@@ -174,7 +178,7 @@ STRESS_SETTINGS = [(kf, p) for kf in (0.02, 0.05, 0.10) for p in (0.5, 0.8, 0.95
 def test_mask_stress_sweep():
     """Near-uniform rows (thousands of near-ties) and sink-dominated rows: on every head and every setting the mask
     must equal the oracle's selection on the exported scores; flips are counted per setting.  Attention samples on
-    four of the nine settings, two heads each."""
+    four of the nine settings."""
     w = wl.MASK_STRESS
     print(f"workload {w.name}: B={w.B} H={w.H} N={w.N} d={w.d}", flush=True)
     q, k, v, do = wl.make_inputs(w, seed=0, device=dev())
@@ -191,9 +195,12 @@ def test_mask_stress_sweep():
                 if key.startswith("stage") and key != "stage1_max_rel":
                     tot[key] = tot.get(key, 0) + val
         print(f"  k={kf} p={p}: k_cnt={k_cnt} density={float(pat.mask.float().mean()):.4f} flips over {len(ref_pbar)} heads={tot}", flush=True)
-        if si in (0, 1, 5, 8):      # attention spot checks: sparsest, the default, a mixed and the densest setting
-            for (b, h) in ((1, 7), (0, 3)):
-                cc = pat.col_cnt[b, h].cpu().numpy()
-                _check_head_samples(w, b, h, q, k, v, do, pat, o, lse, dq, dk, dv,
-                                    q_blocks=[0, 1, w.Tm - 1], kv_blocks=[0, int(cc[1:].argmax()) + 1])
+        # attention spot checks on four settings (sparsest, the default p, a mixed and the densest one).  The sink key
+        # block (block 0, selected by every other query block at least) is the expensive one for the oracle: it is
+        # checked on the two sparser settings, an ordinary hot key block on all four.
+        plan = {0: [((1, 7), True), ((0, 3), True)], 1: [((1, 7), True)], 5: [((0, 3), False)], 8: [((1, 7), False)]}
+        for (b, h), with_sink in plan.get(si, []):
+            cc = pat.col_cnt[b, h].cpu().numpy()
+            _check_head_samples(w, b, h, q, k, v, do, pat, o, lse, dq, dk, dv, q_blocks=[0, 1, w.Tm - 1],
+                                kv_blocks=([0] if with_sink else []) + [int(cc[1:].argmax()) + 1])
     _print_tally(w.name)
