@@ -111,6 +111,7 @@ def main():
     pat = spa2.alloc_pattern(w.B, w.H, w.N, dev)
     ws_m = torch.empty(spa2.spa2_mask_workspace_bytes(q), dtype=torch.uint8, device=dev)
     ws_b = torch.empty(spa2.spa2_bwd_workspace_bytes(q), dtype=torch.uint8, device=dev)
+    ws_f = torch.empty(spa2.spa2_fwd_workspace_bytes(q), dtype=torch.uint8, device=dev)
     k_cnt = spa2.spa2_topk_blocks(w.k_frac, w.Tn)
 
     stages = ["pool", "select", "columns", "fwd", "delta", "dkdv", "dq"]
@@ -123,7 +124,7 @@ def main():
         spa2.spa2_mask_pool(q, k, ws_m); mark(1)
         spa2.spa2_mask_select(q, k_cnt, w.top_p, scale, p, None, ws_m); mark(2)
         spa2.spa2_mask_columns(q, p); mark(3)
-        spa2.spa2_fwd(q, k, v, p, scale, o, lse, o_res); mark(4)
+        spa2.spa2_fwd(q, k, v, p, scale, o, lse, o_res, ws_f); mark(4)
         if w.backward:        # a forward-only configuration stops here (its stage times below read 0)
             spa2.spa2_bwd_delta(o, do, ws_b, o_res); mark(5)
             spa2.spa2_bwd_dkdv(q, k, v, do, lse, p, scale, dk, dv, ws_b); mark(6)
@@ -201,7 +202,7 @@ def main():
             spa2.spa2_mask_pool(q, k, ws_m)
             spa2.spa2_mask_select(q, k_cnt, w.top_p, scale, pat, None, ws_m)
             spa2.spa2_mask_columns(q, pat)
-            spa2.spa2_fwd(q, k, v, pat, scale, o, lse, o_res)
+            spa2.spa2_fwd(q, k, v, pat, scale, o, lse, o_res, ws_f)
             backward_two_streams(q, k, v, o, do, lse, pat, scale, dq, dk, dv, ws_b, o_res)
         overlapped_step()
         torch.cuda.synchronize()
@@ -219,7 +220,7 @@ def main():
         spa2.spa2_pattern_full(q, full)
 
         def dense_step():
-            spa2.spa2_fwd(q, k, v, full, scale, o, lse, o_res)
+            spa2.spa2_fwd(q, k, v, full, scale, o, lse, o_res, ws_f)
             if w.backward:
                 spa2.spa2_bwd(q, k, v, o, do, lse, full, scale, dq, dk, dv, ws_b, o_res)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

@@ -95,9 +95,17 @@ const char* spa2_strerror(int code);
  * entries keeps two) fixes the integral case. */
 int32_t spa2_topk_blocks(double k_frac, int32_t Tn);
 
-/* Bytes of device scratch spa2_mask / spa2_bwd need for this shape. */
+/* Bytes of device scratch spa2_mask / spa2_fwd / spa2_bwd use for this shape (0 = bad shape).
+ *   spa2_mask_workspace_bytes      mandatory for spa2_mask and its stages (pooled means).
+ *   spa2_fwd_workspace_bytes       optional for spa2_fwd (see there): plan and partial results of split rows.
+ *   spa2_bwd_workspace_bytes       full backward workspace: D, then plans and partial results of split rows
+ *                                  (dQ) and split columns (dK, dV).
+ *   spa2_bwd_workspace_min_bytes   the mandatory leading part of it (D only).  With a buffer between the two
+ *                                  sizes the backward kernels split as many lists as the rest of it holds. */
 size_t spa2_mask_workspace_bytes(const spa2_shape* shape);
+size_t spa2_fwd_workspace_bytes(const spa2_shape* shape);
 size_t spa2_bwd_workspace_bytes(const spa2_shape* shape);
+size_t spa2_bwd_workspace_min_bytes(const spa2_shape* shape);
 
 /* Alg. 1 steps 2-6 (Sec. 2.2 pooling and pooled map, Sec. 4.1 hybrid rule).
  *   q, k        bf16 token tensors (device).
@@ -145,15 +153,24 @@ int spa2_pattern_full(const spa2_shape* shape, spa2_pattern* out, void* stream);
  *          result that the rounding of o to bf16 dropped, o_res = bf16(O_fp32 - o).  The backward pass
  *          uses o + o_res for D = rowsum(dO * O); with o alone, the 2^-9 relative rounding of O is the
  *          largest error term of dQ when |K| is large.
+ *   workspace  optional (NULL, 0 = none), 16-byte aligned, up to spa2_fwd_workspace_bytes(shape) bytes.  One
+ *          workgroup walks one row of the pattern, so a launch cannot end before its longest row has; on layers
+ *          with few rows per compute unit the longest rows then set the time.  With a workspace, lists longer than
+ *          S = max(16, total tiles / 2048) entries are cut into parts of S that run as workgroups of their own;
+ *          the parts' (O, m, l) are combined in part order by a second kernel (Alg. 1 step 18 makes that exact up
+ *          to rounding), so results stay deterministic.  On large layers S exceeds every list and nothing changes.
  * Reads pattern->row_cnt / row_idx (and row_order if set). */
 int spa2_fwd(const void* q, const void* k, const void* v, const spa2_shape* shape,
-             const spa2_pattern* pattern, float scale, void* o, void* o_res, float* lse, void* stream);
+             const spa2_pattern* pattern, float scale, void* o, void* o_res, float* lse,
+             void* workspace, size_t workspace_bytes, void* stream);
 
 /* Backward of spa2_fwd for upstream gradient d_o, mask held constant.  With
  * P = exp(S - lse) on selected tiles:  dV = P^T dO,  dP = dO V^T,
  * D = rowsum(dO * O),  dS = P * (dP - D),  dQ = dS K * scale,  dK = dS^T Q * scale.
  *   dq, dk, dv  bf16 token tensors (written everywhere, zeros where no tile contributes).
- * Reads row_* (dQ) and col_* (dK, dV) of the pattern; workspace holds D. */
+ * Reads row_* (dQ) and col_* (dK, dV) of the pattern.  workspace: at least spa2_bwd_workspace_min_bytes (D);
+ * with up to spa2_bwd_workspace_bytes, long rows (dQ) and long columns (dK, dV) are cut into parts as in spa2_fwd
+ * and their fp32 partial sums are added in part order. */
 int spa2_bwd(const void* q, const void* k, const void* v, const void* o, const void* o_res /* or NULL */,
              const void* d_o, const float* lse, const spa2_shape* shape, const spa2_pattern* pattern,
              float scale, void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes, void* stream);
@@ -163,15 +180,16 @@ int spa2_bwd(const void* q, const void* k, const void* v, const void* o, const v
  *   spa2_bwd_delta  D = rowsum(dO * (o + o_res)), fp32 [B,H,N], left in `workspace`;
  *   spa2_bwd_dkdv   dK, dV: one pass per key block over the query blocks listed in col_idx;
  *   spa2_bwd_dq     dQ: one pass per query block over the key blocks listed in row_idx.
- * dkdv and dq read D from `workspace` (written by spa2_bwd_delta for the same o, d_o). */
+ * dkdv and dq read D from `workspace` (written by spa2_bwd_delta for the same o, d_o) and keep their split plans
+ * and partial sums in their own sections behind it, so the two may run at the same time on two streams. */
 int spa2_bwd_delta(const void* o, const void* o_res /* or NULL */, const void* d_o, const spa2_shape* shape,
                    void* workspace, size_t workspace_bytes, void* stream);
 int spa2_bwd_dkdv(const void* q, const void* k, const void* v, const void* d_o, const float* lse,
                   const spa2_shape* shape, const spa2_pattern* pattern, float scale,
-                  void* dk, void* dv, const void* workspace, size_t workspace_bytes, void* stream);
+                  void* dk, void* dv, void* workspace, size_t workspace_bytes, void* stream);
 int spa2_bwd_dq(const void* q, const void* k, const void* v, const void* d_o, const float* lse,
                 const spa2_shape* shape, const spa2_pattern* pattern, float scale,
-                void* dq, const void* workspace, size_t workspace_bytes, void* stream);
+                void* dq, void* workspace, size_t workspace_bytes, void* stream);
 
 /* spa2_bwd for callers that cannot provide or allocate a workspace (code under HIP graph capture, tight serving
  * loops, harnesses that forbid hipMalloc): same arguments, results and error behaviour as spa2_bwd, without the
@@ -179,6 +197,7 @@ int spa2_bwd_dq(const void* q, const void* k, const void* v, const void* d_o, co
  * memory of every GPU it runs on until the process ends; no allocation happens in this call (the array's device
  * address is looked up on the first call on each device, with the calling thread's current device).
  *   Limit: B * H * N <= SPA2_STATIC_MAX_ROWS, otherwise SPA2_ERR_WORKSPACE and nothing is launched.
+ *   Long rows and columns are not split on this path (that needs the larger workspace of spa2_bwd).
  *   All calls on one GPU share that array: two calls whose execution overlaps on one GPU (different streams,
  *   different threads) race on D and give wrong gradients; calls on one stream are safe.  The array keeps the
  *   last call's D; every row a call reads is written by that same call first. */

@@ -7,7 +7,7 @@ distillation step with its fused loss; `workloads` holds the seeded
 synthetic input recipes; `build` compiles the library in-tree with hipcc.
 """
 from .binding import (  # noqa: F401
-    BKV, BQ, Pattern, Spa2Error, alloc_pattern, spa2_bwd, spa2_bwd_static, spa2_bwd_workspace_bytes, spa2_fwd, spa2_mask,
+    BKV, BQ, Pattern, Spa2Error, alloc_pattern, spa2_bwd, spa2_bwd_static, spa2_bwd_workspace_bytes, spa2_bwd_workspace_min_bytes, spa2_fwd_workspace_bytes, spa2_fwd, spa2_mask,
     spa2_mask_workspace_bytes, spa2_pattern_full, spa2_mask_pool, spa2_mask_select, spa2_mask_columns,
     spa2_bwd_delta, spa2_bwd_dkdv, spa2_bwd_dq, spa2_error_terms, spa2_error_workspace_bytes, spa2_strerror,
     spa2_topk_blocks, spa2_version, spa2_vd_loss, spa2_vd_loss_grad, spa2_vd_loss_workspace_bytes,

@@ -92,7 +92,8 @@ class _SpargeAttn2(torch.autograd.Function):
         B, H, N, _ = q.shape
         o, o_res = _like(q), _like(q)
         lse = torch.empty((B, H, N), dtype=torch.float32, device=q.device)
-        _b.spa2_fwd(q, k, v, pattern, scale, o, lse, o_res)
+        ws_f = torch.empty(_b.spa2_fwd_workspace_bytes(q), dtype=torch.uint8, device=q.device)   # long rows split
+        _b.spa2_fwd(q, k, v, pattern, scale, o, lse, o_res, ws_f)
         ctx.save_for_backward(q, k, v, o, o_res, lse)
         ctx.pattern, ctx.scale, ctx.overlap = pattern, scale, bool(overlap_backward)
         return o

@@ -64,12 +64,16 @@ def _load():
     lib.spa2_mask_workspace_bytes.argtypes = [shp]
     lib.spa2_bwd_workspace_bytes.restype = sz
     lib.spa2_bwd_workspace_bytes.argtypes = [shp]
+    lib.spa2_bwd_workspace_min_bytes.restype = sz
+    lib.spa2_bwd_workspace_min_bytes.argtypes = [shp]
+    lib.spa2_fwd_workspace_bytes.restype = sz
+    lib.spa2_fwd_workspace_bytes.argtypes = [shp]
     lib.spa2_mask.restype = ctypes.c_int
     lib.spa2_mask.argtypes = [vp, vp, shp, i32, f32, f32, pat, vp, vp, sz, vp]
     lib.spa2_pattern_full.restype = ctypes.c_int
     lib.spa2_pattern_full.argtypes = [shp, pat, vp]
     lib.spa2_fwd.restype = ctypes.c_int
-    lib.spa2_fwd.argtypes = [vp, vp, vp, shp, pat, f32, vp, vp, vp, vp]
+    lib.spa2_fwd.argtypes = [vp, vp, vp, shp, pat, f32, vp, vp, vp, vp, sz, vp]
     lib.spa2_bwd.restype = ctypes.c_int
     lib.spa2_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, shp, pat, f32, vp, vp, vp, vp, sz, vp]
     lib.spa2_bwd_static.restype = ctypes.c_int
@@ -101,7 +105,7 @@ def _load():
 
 
 EXPORTED_SYMBOLS = ("spa2_version", "spa2_strerror", "spa2_topk_blocks", "spa2_mask_workspace_bytes",
-                    "spa2_bwd_workspace_bytes", "spa2_mask", "spa2_mask_pool", "spa2_mask_select",
+                    "spa2_bwd_workspace_bytes", "spa2_bwd_workspace_min_bytes", "spa2_fwd_workspace_bytes", "spa2_mask", "spa2_mask_pool", "spa2_mask_select",
                     "spa2_mask_columns", "spa2_pattern_full", "spa2_fwd", "spa2_bwd", "spa2_bwd_static", "spa2_bwd_delta",
                     "spa2_bwd_dkdv", "spa2_bwd_dq", "spa2_error_workspace_bytes", "spa2_error_terms",
                     "spa2_vd_loss_workspace_bytes", "spa2_vd_loss", "spa2_vd_loss_grad")
@@ -187,6 +191,14 @@ def spa2_bwd_workspace_bytes(q: torch.Tensor) -> int:
     return int(_load().spa2_bwd_workspace_bytes(ctypes.byref(_shape_of(q))))
 
 
+def spa2_bwd_workspace_min_bytes(q: torch.Tensor) -> int:
+    return int(_load().spa2_bwd_workspace_min_bytes(ctypes.byref(_shape_of(q))))
+
+
+def spa2_fwd_workspace_bytes(q: torch.Tensor) -> int:
+    return int(_load().spa2_fwd_workspace_bytes(ctypes.byref(_shape_of(q))))
+
+
 def spa2_mask(q: torch.Tensor, k: torch.Tensor, topk_blocks: int, top_p: float, scale: float,
               out: Pattern, pbar_out: Optional[torch.Tensor], workspace: torch.Tensor) -> None:
     _same_layout(q, k)
@@ -206,13 +218,15 @@ def spa2_pattern_full(like: torch.Tensor, out: Pattern) -> None:
 
 
 def spa2_fwd(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, pattern: Pattern, scale: float,
-             o: torch.Tensor, lse: torch.Tensor, o_res: Optional[torch.Tensor] = None) -> None:
+             o: torch.Tensor, lse: torch.Tensor, o_res: Optional[torch.Tensor] = None,
+             workspace: Optional[torch.Tensor] = None) -> None:
     _same_layout(q, k, v, o, *([o_res] if o_res is not None else []))
     shape = _shape_of(q)
     pat = pattern._c()
     rc = _load().spa2_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), ctypes.byref(shape), ctypes.byref(pat),
                           float(scale), o.data_ptr(), o_res.data_ptr() if o_res is not None else None,
-                          lse.data_ptr(), _stream(q))
+                          lse.data_ptr(), workspace.data_ptr() if workspace is not None else None,
+                          _nbytes(workspace) if workspace is not None else 0, _stream(q))
     _check(rc, "spa2_fwd")
 
 

@@ -15,7 +15,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 BUILD = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libspa2.so")
-SOURCES = ["api.hip", "mask.hip", "fwd.hip", "bwd.hip", "bwd_dkdv.hip", "diag.hip", "distill.hip"]
+SOURCES = ["api.hip", "mask.hip", "fwd.hip", "bwd.hip", "bwd_dkdv.hip", "split.hip", "diag.hip", "distill.hip"]
 # per-file flags: the dK/dV kernel mixes matrix products whose results the vector ALU reads (kept in ordinary
 # registers by this option) with accumulators that it pins to the accumulation registers itself
 EXTRA = {"bwd_dkdv.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}

@@ -40,7 +40,27 @@ MaskWs mask_ws(const Dims& m) {
   return w;
 }
 
-size_t bwd_ws_bytes(const Dims& m) { return round256((size_t)m.B * m.H * m.N * sizeof(float)); }
+// Backward workspace: D (fp32, one value per token row), then the split plans and partial-result pools of the dQ
+// and the dK/dV kernel.  Only D is mandatory: with less than the full size the kernels walk every list whole.
+struct BwdWs { size_t d_bytes, dq_off, dq_bytes, dkdv_off, dkdv_bytes, total; };
+BwdWs bwd_ws(const Dims& m) {
+  BwdWs w;
+  w.d_bytes = round256((size_t)m.B * m.H * m.N * sizeof(float));
+  w.dq_off = w.d_bytes;
+  w.dq_bytes = round256(split_ws_bytes((int64_t)m.B * m.H * m.Tm, dq_slot_bytes(m)));
+  w.dkdv_off = w.dq_off + w.dq_bytes;
+  w.dkdv_bytes = round256(split_ws_bytes((int64_t)m.B * m.H * m.Tn, dkdv_slot_bytes(m)));
+  w.total = w.dkdv_off + w.dkdv_bytes;
+  return w;
+}
+size_t bwd_ws_min_bytes(const Dims& m) { return bwd_ws(m).d_bytes; }
+
+// the part of a workspace section that the caller's buffer really covers
+SplitPlan section_plan(void* ws, size_t ws_bytes, size_t off, size_t bytes, int64_t units, size_t slot_bytes) {
+  if (!ws || ws_bytes <= off) return split_layout(nullptr, 0, units, slot_bytes);
+  const size_t have = ws_bytes - off < bytes ? ws_bytes - off : bytes;
+  return split_layout((char*)ws + off, have, units, slot_bytes);
+}
 
 }  // namespace
 
@@ -77,7 +97,18 @@ size_t spa2_mask_workspace_bytes(const spa2_shape* shape) {
 
 size_t spa2_bwd_workspace_bytes(const spa2_shape* shape) {
   if (check_shape(shape) != SPA2_OK) return 0;
-  return bwd_ws_bytes(make_dims(*shape));
+  return bwd_ws(make_dims(*shape)).total;
+}
+
+size_t spa2_bwd_workspace_min_bytes(const spa2_shape* shape) {
+  if (check_shape(shape) != SPA2_OK) return 0;
+  return bwd_ws_min_bytes(make_dims(*shape));
+}
+
+size_t spa2_fwd_workspace_bytes(const spa2_shape* shape) {
+  if (check_shape(shape) != SPA2_OK) return 0;
+  const Dims m = make_dims(*shape);
+  return round256(split_ws_bytes((int64_t)m.B * m.H * m.Tm, fwd_slot_bytes(m)));
 }
 
 int spa2_mask_pool(const void* q, const void* k, const spa2_shape* shape, void* workspace,
@@ -163,14 +194,17 @@ int spa2_pattern_full(const spa2_shape* shape, spa2_pattern* out, void* stream) 
 }
 
 int spa2_fwd(const void* q, const void* k, const void* v, const spa2_shape* shape, const spa2_pattern* pattern,
-             float scale, void* o, void* o_res, float* lse, void* stream) {
+             float scale, void* o, void* o_res, float* lse, void* workspace, size_t workspace_bytes, void* stream) {
   int rc = check_shape(shape);
   if (rc != SPA2_OK) return rc;
   if (!q || !k || !v || !o || !lse || !pattern || !pattern->row_cnt || !pattern->row_idx) return SPA2_ERR_NULL;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(o_res)) return SPA2_ERR_ALIGN;
   if (!(scale > 0.f) || !isfinite(scale)) return SPA2_ERR_RANGE;
+  if (workspace && !aligned16(workspace)) return SPA2_ERR_ALIGN;
   const Dims m = make_dims(*shape);
-  if (launch_fwd(q, k, v, m, pattern->row_cnt, pattern->row_idx, pattern->row_order, scale, o, o_res, lse,
+  const SplitPlan plan = section_plan(workspace, workspace_bytes, 0, spa2_fwd_workspace_bytes(shape),
+                                      (int64_t)m.B * m.H * m.Tm, fwd_slot_bytes(m));
+  if (launch_fwd(q, k, v, m, pattern->row_cnt, pattern->row_idx, pattern->row_order, scale, o, o_res, lse, plan,
                  (hipStream_t)stream) != hipSuccess)
     return SPA2_ERR_LAUNCH;
   return SPA2_OK;
@@ -183,7 +217,7 @@ int spa2_bwd_delta(const void* o, const void* o_res, const void* d_o, const spa2
   if (!o || !d_o) return SPA2_ERR_NULL;
   if (!aligned16(o) || !aligned16(d_o) || !aligned16(o_res)) return SPA2_ERR_ALIGN;
   const Dims m = make_dims(*shape);
-  if (!workspace || workspace_bytes < bwd_ws_bytes(m)) return SPA2_ERR_WORKSPACE;
+  if (!workspace || workspace_bytes < bwd_ws_min_bytes(m)) return SPA2_ERR_WORKSPACE;
   if (!aligned16(workspace)) return SPA2_ERR_ALIGN;
   return launch_bwd_delta(o, o_res, d_o, m, (float*)workspace, (hipStream_t)stream) == hipSuccess ? SPA2_OK
                                                                                            : SPA2_ERR_LAUNCH;
@@ -191,7 +225,7 @@ int spa2_bwd_delta(const void* o, const void* o_res, const void* d_o, const spa2
 
 int spa2_bwd_dkdv(const void* q, const void* k, const void* v, const void* d_o, const float* lse,
                   const spa2_shape* shape, const spa2_pattern* pattern, float scale, void* dk, void* dv,
-                  const void* workspace, size_t workspace_bytes, void* stream) {
+                  void* workspace, size_t workspace_bytes, void* stream) {
   int rc = check_shape(shape);
   if (rc != SPA2_OK) return rc;
   if (!q || !k || !v || !d_o || !lse || !dk || !dv || !pattern || !pattern->col_cnt || !pattern->col_idx)
@@ -200,15 +234,18 @@ int spa2_bwd_dkdv(const void* q, const void* k, const void* v, const void* d_o, 
     return SPA2_ERR_ALIGN;
   if (!(scale > 0.f) || !isfinite(scale)) return SPA2_ERR_RANGE;
   const Dims m = make_dims(*shape);
-  if (!workspace || workspace_bytes < bwd_ws_bytes(m)) return SPA2_ERR_WORKSPACE;
+  if (!workspace || workspace_bytes < bwd_ws_min_bytes(m)) return SPA2_ERR_WORKSPACE;
   if (!aligned16(workspace)) return SPA2_ERR_ALIGN;
+  const BwdWs w = bwd_ws(m);
+  const SplitPlan plan = section_plan(workspace, workspace_bytes, w.dkdv_off, w.dkdv_bytes, (int64_t)m.B * m.H * m.Tn,
+                                      dkdv_slot_bytes(m));
   return launch_bwd_dkdv(q, k, v, d_o, lse, (const float*)workspace, m, pattern->col_cnt, pattern->col_idx,
-                         pattern->col_order, scale, dk, dv, (hipStream_t)stream) == hipSuccess ? SPA2_OK : SPA2_ERR_LAUNCH;
+                         pattern->col_order, scale, dk, dv, plan, (hipStream_t)stream) == hipSuccess ? SPA2_OK : SPA2_ERR_LAUNCH;
 }
 
 int spa2_bwd_dq(const void* q, const void* k, const void* v, const void* d_o, const float* lse,
                 const spa2_shape* shape, const spa2_pattern* pattern, float scale, void* dq,
-                const void* workspace, size_t workspace_bytes, void* stream) {
+                void* workspace, size_t workspace_bytes, void* stream) {
   int rc = check_shape(shape);
   if (rc != SPA2_OK) return rc;
   if (!q || !k || !v || !d_o || !lse || !dq || !pattern || !pattern->row_cnt || !pattern->row_idx)
@@ -216,10 +253,13 @@ int spa2_bwd_dq(const void* q, const void* k, const void* v, const void* d_o, co
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(d_o) || !aligned16(dq)) return SPA2_ERR_ALIGN;
   if (!(scale > 0.f) || !isfinite(scale)) return SPA2_ERR_RANGE;
   const Dims m = make_dims(*shape);
-  if (!workspace || workspace_bytes < bwd_ws_bytes(m)) return SPA2_ERR_WORKSPACE;
+  if (!workspace || workspace_bytes < bwd_ws_min_bytes(m)) return SPA2_ERR_WORKSPACE;
   if (!aligned16(workspace)) return SPA2_ERR_ALIGN;
+  const BwdWs w = bwd_ws(m);
+  const SplitPlan plan = section_plan(workspace, workspace_bytes, w.dq_off, w.dq_bytes, (int64_t)m.B * m.H * m.Tm,
+                                      dq_slot_bytes(m));
   return launch_bwd_dq(q, k, v, d_o, lse, (const float*)workspace, m, pattern->row_cnt, pattern->row_idx,
-                       pattern->row_order, scale, dq, (hipStream_t)stream) == hipSuccess ? SPA2_OK : SPA2_ERR_LAUNCH;
+                       pattern->row_order, scale, dq, plan, (hipStream_t)stream) == hipSuccess ? SPA2_OK : SPA2_ERR_LAUNCH;
 }
 
 int spa2_bwd(const void* q, const void* k, const void* v, const void* o, const void* o_res, const void* d_o,
@@ -234,7 +274,7 @@ int spa2_bwd(const void* q, const void* k, const void* v, const void* o, const v
     return SPA2_ERR_ALIGN;
   if (!(scale > 0.f) || !isfinite(scale)) return SPA2_ERR_RANGE;
   const Dims m = make_dims(*shape);
-  if (!workspace || workspace_bytes < bwd_ws_bytes(m)) return SPA2_ERR_WORKSPACE;
+  if (!workspace || workspace_bytes < bwd_ws_min_bytes(m)) return SPA2_ERR_WORKSPACE;
   if (!aligned16(workspace)) return SPA2_ERR_ALIGN;
   rc = spa2_bwd_delta(o, o_res, d_o, shape, workspace, workspace_bytes, stream);
   if (rc != SPA2_OK) return rc;
@@ -332,6 +372,7 @@ extern "C" int spa2_bwd_static(const void* q, const void* k, const void* v, cons
   rc = scratch_for_current_device(&ws);
   if (rc != SPA2_OK) return rc;
   // every row of D that the kernels read is written by the delta pass of this same call: nothing to clear
+  // exactly the mandatory part of the workspace: long rows and columns are not split on this path
   return spa2_bwd(q, k, v, o, o_res, d_o, lse, shape, pattern, scale, dq, dk, dv, ws,
-                  (size_t)SPA2_STATIC_MAX_ROWS * sizeof(float), stream);
+                  spa2_bwd_workspace_min_bytes(shape), stream);
 }

@@ -80,7 +80,29 @@ struct DqArgs {
   int H, N, Tm, Tn, chunk;
   int64_t sb, sh, sn;
   float scale, scale_log2;
+  SplitPlan sp;         // long rows cut into parts (split.hip); sp.pool_slots == 0: every row is walked whole
 };
+
+// Partial result of one part of a split row: the fp32 accumulator of every thread of the workgroup.
+template <int D> constexpr int dq_slot_floats() { return 256 * (D / 2); }
+size_t dq_slot_bytes(const Dims& m) { return (size_t)(m.d == 128 ? dq_slot_floats<128>() : dq_slot_floats<64>()) * 4; }
+
+// dQ = acc * scale -> bf16; a lane owns one query row, accumulator register v of block mb is channel
+// 32 mb + 8 (v / 4) + 4 hf + v % 4.
+template <int D>
+__device__ __forceinline__ void dq_store_rows(const DqArgs& a, int64_t base, int qrow, int hf, const f32x16 (&acc)[D / 32]) {
+  if (qrow < a.N) {
+    uint16_t* op = a.dq + base + (int64_t)qrow * a.sn + 4 * hf;
+#pragma unroll
+    for (int mb = 0; mb < D / 32; ++mb)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        u32x2 pk = {pack_bf16(acc[mb][4 * g + 0] * a.scale, acc[mb][4 * g + 1] * a.scale),
+                    pack_bf16(acc[mb][4 * g + 2] * a.scale, acc[mb][4 * g + 3] * a.scale)};
+        *(u32x2*)(op + 32 * mb + 8 * g) = pk;
+      }
+  }
+}
 
 template <int D>
 struct DqCfg {
@@ -101,16 +123,32 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(DqArgs a) {
   __shared__ __align__(16) uint16_t smem[2 * (C::K_ELEMS + C::V_ELEMS)];   // stage s: K tile, then V tile
   constexpr int STAGE = C::K_ELEMS + C::V_ELEMS;
 
-  const HeadBlock hb = xcd_map(blockIdx.x, a.Tm, a.chunk);
-  if (!hb.valid) return;
-  const int bh = hb.bh;
-  const int i = a.row_order ? min(max(a.row_order[(int64_t)bh * a.Tm + hb.blk], 0), a.Tm - 1) : hb.blk;
+  // Which row, and which part of its list (see fwd.hip: the first sp.pool_slots workgroups are the extra parts)
+  int bh, i, part = 0, slot = -1;
+  if ((int)blockIdx.x < a.sp.pool_slots) {
+    if ((int)blockIdx.x >= a.sp.header[0]) return;
+    const int unit = a.sp.part_table[2 * blockIdx.x];
+    part = a.sp.part_table[2 * blockIdx.x + 1];
+    bh = unit / a.Tm; i = unit % a.Tm;
+    slot = a.sp.unit_slot[unit] + part;
+  } else {
+    const HeadBlock hb = xcd_map(blockIdx.x - a.sp.pool_slots, a.Tm, a.chunk);
+    if (!hb.valid) return;
+    bh = hb.bh;
+    i = a.row_order ? min(max(a.row_order[(int64_t)bh * a.Tm + hb.blk], 0), a.Tm - 1) : hb.blk;
+    if (a.sp.pool_slots) slot = a.sp.unit_slot[(int64_t)bh * a.Tm + i];
+  }
   const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int r32 = lane & 31, hf = lane >> 5;
   const int N = a.N;
-  const int cnt = min(max(a.row_cnt[(int64_t)bh * a.Tm + i], 0), a.Tn);   // clamped: see fwd.hip
+  int cnt = min(max(a.row_cnt[(int64_t)bh * a.Tm + i], 0), a.Tn);   // clamped: see fwd.hip
   const int32_t* idx = a.row_idx + ((int64_t)bh * a.Tm + i) * a.Tn;
+  if (slot >= 0) {            // entries [part * S, (part + 1) * S) of the list
+    const int S = a.sp.header[1];
+    idx += part * S;
+    cnt = min(cnt - part * S, S);
+  }
   const int qrow = i * BQ + w * 32 + r32;
 
   if (cnt == 0) {
@@ -271,22 +309,60 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(DqArgs a) {
     __syncthreads();
   }
 
-  if (qrow < N) {
-    uint16_t* op = a.dq + base + (int64_t)qrow * a.sn + 4 * hf;
+  if (slot >= 0) {            // one part of a split row: leave the partial sum to the merge kernel
+    f32x4* pa = (f32x4*)(a.sp.pool + (int64_t)slot * a.sp.slot_floats + tid * (D / 2));
 #pragma unroll
     for (int mb = 0; mb < D / 32; ++mb)
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        u32x2 pk = {pack_bf16(acc[mb][4 * g + 0] * a.scale, acc[mb][4 * g + 1] * a.scale),
-                    pack_bf16(acc[mb][4 * g + 2] * a.scale, acc[mb][4 * g + 3] * a.scale)};
-        *(u32x2*)(op + 32 * mb + 8 * g) = pk;
-      }
+      for (int g = 0; g < 4; ++g)
+        pa[mb * 4 + g] = f32x4{acc[mb][4 * g], acc[mb][4 * g + 1], acc[mb][4 * g + 2], acc[mb][4 * g + 3]};
+    return;
   }
+  dq_store_rows<D>(a, base, qrow, hf, acc);
+}
+
+// Adds the parts of every split row in part order (fixed order: deterministic).  Same thread -> (row, channel)
+// mapping as dq_kernel; workgroup x takes split row x of the plan.
+template <int D>
+__global__ __launch_bounds__(256) void dq_merge_kernel(DqArgs a) {
+  if ((int)blockIdx.x >= a.sp.header[2]) return;
+  const int unit = a.sp.merge_table[blockIdx.x];
+  const int bh = unit / a.Tm, i = unit % a.Tm;
+  const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int cnt = min(max(a.row_cnt[unit], 0), a.Tn);
+  const int S = a.sp.header[1];
+  const int parts = (cnt + S - 1) / S;
+  const float* p0 = a.sp.pool + (int64_t)a.sp.unit_slot[unit] * a.sp.slot_floats + tid * (D / 2);
+  f32x16 acc[D / 32];
+#pragma unroll
+  for (int mb = 0; mb < D / 32; ++mb)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[mb][v] = 0.f;
+  // two parts per step: the loads of both are in flight together; the order of addition stays part 0, 1, 2, ...
+  for (int p = 0; p < parts; p += 2) {
+    const bool two = p + 1 < parts;
+    const f32x4* pa0 = (const f32x4*)(p0 + (int64_t)p * a.sp.slot_floats);
+    const f32x4* pa1 = (const f32x4*)(p0 + (int64_t)(two ? p + 1 : p) * a.sp.slot_floats);
+    f32x4 x0[D / 8], x1[D / 8];
+#pragma unroll
+    for (int c = 0; c < D / 8; ++c) { x0[c] = pa0[c]; x1[c] = pa1[c]; }
+#pragma unroll
+    for (int mb = 0; mb < D / 32; ++mb)
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          acc[mb][4 * g + e] += x0[mb * 4 + g][e];
+          if (two) acc[mb][4 * g + e] += x1[mb * 4 + g][e];
+        }
+  }
+  dq_store_rows<D>(a, base, i * BQ + w * 32 + (lane & 31), lane >> 5, acc);
 }
 
 hipError_t launch_bwd_dq(const void* q, const void* k, const void* v, const void* d_o, const float* lse,
                          const float* delta, const Dims& m, const int32_t* row_cnt, const int32_t* row_idx,
-                         const int32_t* row_order, float scale, void* dq, hipStream_t stream) {
+                         const int32_t* row_order, float scale, void* dq, const SplitPlan& plan, hipStream_t stream) {
   DqArgs a;
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v; a.d_o = (const uint16_t*)d_o;
   a.lse = lse; a.delta = delta; a.dq = (uint16_t*)dq;
@@ -294,9 +370,19 @@ hipError_t launch_bwd_dq(const void* q, const void* k, const void* v, const void
   a.H = m.H; a.N = m.N; a.Tm = m.Tm; a.Tn = m.Tn; a.chunk = (m.Tm + 7) / 8;
   a.sb = m.sb; a.sh = m.sh; a.sn = m.sn;
   a.scale = scale; a.scale_log2 = scale * LOG2E;
-  const dim3 grid((unsigned)(m.B * m.H * 8 * a.chunk)), block(256);
+  a.sp = plan;
+  if (plan.pool_slots) {
+    const hipError_t e = launch_split_plan(row_cnt, (int64_t)m.B * m.H * m.Tm, m.Tn, SPLIT_MIN_PART, plan, stream);
+    if (e != hipSuccess) return e;
+  }
+  const dim3 grid((unsigned)(plan.pool_slots + m.B * m.H * 8 * a.chunk)), block(256);
   if (m.d == 128) hipLaunchKernelGGL(dq_kernel<128>, grid, block, 0, stream, a);
   else            hipLaunchKernelGGL(dq_kernel<64>, grid, block, 0, stream, a);
+  if (plan.pool_slots) {
+    const dim3 mg((unsigned)(plan.pool_slots / 2));
+    if (m.d == 128) hipLaunchKernelGGL(dq_merge_kernel<128>, mg, block, 0, stream, a);
+    else            hipLaunchKernelGGL(dq_merge_kernel<64>, mg, block, 0, stream, a);
+  }
   return hipGetLastError();
 }
 

@@ -25,7 +25,13 @@ struct DkvArgs {
   int H, N, Tm, Tn, chunk;
   int64_t sb, sh, sn;
   float scale, scale_log2;
+  SplitPlan sp;         // long columns cut into parts (split.hip); sp.pool_slots == 0: every column is walked whole
 };
+
+// Partial result of one part of a split column: the fp32 sums of the two waves, dK^T then dV^T, in the order
+// [tensor][finishing wave][output block][group of four registers][lane][register in the group].
+template <int D> constexpr int dkdv_slot_floats() { return 2 * 2 * (D / 32) * 16 * 64; }
+size_t dkdv_slot_bytes(const Dims& m) { return (size_t)(m.d == 128 ? dkdv_slot_floats<128>() : dkdv_slot_floats<64>()) * 4; }
 
 // One workgroup of two waves per key block j (64 keys); one wave per SIMD (512 registers), four waves per CU.
 // The query blocks that selected j are taken in halves of 64 rows; wave w owns the 32 queries 32w.. of the half
@@ -75,17 +81,34 @@ void dkdv_kernel(DkvArgs a) {
   constexpr int VL = D == 128 ? DKDV_VL : 0;    // fragment f = kh * NK + kk of V^T is in LDS when f >= 2 NK - VL
   __shared__ __align__(1024) unsigned char vfrag_s[(VL ? VL : 1) * 1024];
 
-  const HeadBlock hbk = xcd_map(blockIdx.x, a.Tn, a.chunk);
-  if (!hbk.valid) return;
-  const int bh = hbk.bh;
-  const int j = a.col_order ? min(max(a.col_order[(int64_t)bh * a.Tn + hbk.blk], 0), a.Tn - 1) : hbk.blk;
+  // Which key block, and which part of its list (the first sp.pool_slots workgroups of the launch are the extra
+  // parts of split columns, part >= 1; the others take one key block each: the whole list, or part 0)
+  int bh, j, part = 0, slot = -1;
+  if ((int)blockIdx.x < a.sp.pool_slots) {
+    if ((int)blockIdx.x >= a.sp.header[0]) return;
+    const int unit = a.sp.part_table[2 * blockIdx.x];
+    part = a.sp.part_table[2 * blockIdx.x + 1];
+    bh = unit / a.Tn; j = unit % a.Tn;
+    slot = a.sp.unit_slot[unit] + part;
+  } else {
+    const HeadBlock hbk = xcd_map(blockIdx.x - a.sp.pool_slots, a.Tn, a.chunk);
+    if (!hbk.valid) return;
+    bh = hbk.bh;
+    j = a.col_order ? min(max(a.col_order[(int64_t)bh * a.Tn + hbk.blk], 0), a.Tn - 1) : hbk.blk;
+    if (a.sp.pool_slots) slot = a.sp.unit_slot[(int64_t)bh * a.Tn + j];
+  }
   const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform, in a scalar register
   const int r32 = lane & 31, hf = lane >> 5;
   const int N = a.N;
-  const int cnt = min(max(a.col_cnt[(int64_t)bh * a.Tn + j], 0), a.Tm);   // clamped: see fwd.hip
+  int cnt = min(max(a.col_cnt[(int64_t)bh * a.Tn + j], 0), a.Tm);   // clamped: see fwd.hip
   const int32_t* idx = a.col_idx + ((int64_t)bh * a.Tn + j) * a.Tm;
+  if (slot >= 0) {            // entries [part * S, (part + 1) * S) of the list
+    const int S = a.sp.header[1];
+    idx += part * S;
+    cnt = min(cnt - part * S, S);
+  }
 
   const int key0 = j * BKV + r32;                    // this lane's key of half 0; half 1 is 32 further
   const bool keys_short = (j + 1) * BKV > N;         // uniform: the block reaches past the last token
@@ -343,7 +366,7 @@ void dkdv_kernel(DkvArgs a) {
         for (int v = 0; v < 16; ++v)
           mine[((kh * NMB + mb) * 16 + v) * 64] = round == 0 ? dk_acc[kh][mb][v] : dv_acc[kh][mb][v];
     __syncthreads();
-    if (key < N) {
+    if (key < N || slot >= 0) {     // (a part writes its whole slot, so that the merge never reads stale sums)
       const int64_t out_off = base + (int64_t)key * a.sn + 4 * hf;
       const float sc = round == 0 ? a.scale : 1.f;
 #pragma unroll
@@ -355,9 +378,14 @@ void dkdv_kernel(DkvArgs a) {
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const int at = ((w * NMB + mb) * 16 + 4 * g + e) * 64 + lane;
-            x[e] = (scratch[at] + scratch[REGION + at]) * sc;
+            x[e] = scratch[at] + scratch[REGION + at];
           }
-          u32x2 pk2 = {pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3])};
+          if (slot >= 0) {      // one part of a split column: leave the sums to the merge kernel
+            float* ps = a.sp.pool + (int64_t)slot * a.sp.slot_floats + ((((round * 2 + w) * NMB + mb) * 4 + g) * 64 + lane) * 4;
+            *(f32x4*)ps = f32x4{x[0], x[1], x[2], x[3]};
+            continue;
+          }
+          u32x2 pk2 = {pack_bf16(x[0] * sc, x[1] * sc), pack_bf16(x[2] * sc, x[3] * sc)};
           *(u32x2*)(out + 8 * g) = pk2;
         }
       }
@@ -366,9 +394,55 @@ void dkdv_kernel(DkvArgs a) {
   }
 }
 
+// Adds the parts of every split column in part order (fixed order: deterministic) and stores dK, dV.  Same thread
+// -> (key, channel) mapping as the end of dkdv_kernel; workgroup x takes split column x of the plan.
+template <int D>
+__global__ __launch_bounds__(128) void dkdv_merge_kernel(DkvArgs a) {
+  constexpr int NMB = D / 32;
+  if ((int)blockIdx.x >= a.sp.header[2]) return;
+  const int unit = a.sp.merge_table[blockIdx.x];
+  const int bh = unit / a.Tn, j = unit % a.Tn;
+  const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, r32 = lane & 31, hf = lane >> 5;
+  const int cnt = min(max(a.col_cnt[unit], 0), a.Tm);
+  const int S = a.sp.header[1];
+  const int parts = (cnt + S - 1) / S;
+  const float* p0 = a.sp.pool + (int64_t)a.sp.unit_slot[unit] * a.sp.slot_floats;
+  const int key = j * BKV + r32 + 32 * w;
+  if (key >= a.N) return;
+  const int64_t out_off = base + (int64_t)key * a.sn + 4 * hf;
+  // all sums of this thread at once, part after part (the 16-byte loads of one part are in flight together)
+  f32x4 x[2 * NMB * 4];
+#pragma unroll
+  for (int c = 0; c < 2 * NMB * 4; ++c) x[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int p = 0; p < parts; ++p) {
+    const f32x4* ps = (const f32x4*)(p0 + (int64_t)p * a.sp.slot_floats) + lane;
+#pragma unroll
+    for (int round = 0; round < 2; ++round)
+#pragma unroll
+      for (int c = 0; c < NMB * 4; ++c)
+        x[round * NMB * 4 + c] += ps[((round * 2 + w) * NMB * 4 + c) * 64];
+  }
+#pragma unroll
+  for (int round = 0; round < 2; ++round) {
+    const float sc = round == 0 ? a.scale : 1.f;
+#pragma unroll
+    for (int mb = 0; mb < NMB; ++mb) {
+      uint16_t* out = (round == 0 ? a.dk : a.dv) + out_off + 32 * mb;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const f32x4 y = x[round * NMB * 4 + mb * 4 + g];
+        u32x2 pk2 = {pack_bf16(y[0] * sc, y[1] * sc), pack_bf16(y[2] * sc, y[3] * sc)};
+        *(u32x2*)(out + 8 * g) = pk2;
+      }
+    }
+  }
+}
+
 hipError_t launch_bwd_dkdv(const void* q, const void* k, const void* v, const void* d_o, const float* lse,
                            const float* delta, const Dims& m, const int32_t* col_cnt, const int32_t* col_idx,
-                           const int32_t* col_order, float scale, void* dk, void* dv, hipStream_t stream) {
+                           const int32_t* col_order, float scale, void* dk, void* dv, const SplitPlan& plan,
+                           hipStream_t stream) {
   DkvArgs a;
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v; a.d_o = (const uint16_t*)d_o;
   a.lse = lse; a.delta = delta; a.dk = (uint16_t*)dk; a.dv = (uint16_t*)dv;
@@ -376,9 +450,19 @@ hipError_t launch_bwd_dkdv(const void* q, const void* k, const void* v, const vo
   a.H = m.H; a.N = m.N; a.Tm = m.Tm; a.Tn = m.Tn; a.chunk = (m.Tn + 7) / 8;
   a.sb = m.sb; a.sh = m.sh; a.sn = m.sn;
   a.scale = scale; a.scale_log2 = scale * LOG2E;
-  const dim3 grid((unsigned)(m.B * m.H * 8 * a.chunk)), block(128);
+  a.sp = plan;
+  if (plan.pool_slots) {
+    const hipError_t e = launch_split_plan(col_cnt, (int64_t)m.B * m.H * m.Tn, m.Tm, SPLIT_MIN_PART / 2, plan, stream);
+    if (e != hipSuccess) return e;
+  }
+  const dim3 grid((unsigned)(plan.pool_slots + m.B * m.H * 8 * a.chunk)), block(128);
   if (m.d == 128) hipLaunchKernelGGL(dkdv_kernel<128>, grid, block, 0, stream, a);
   else            hipLaunchKernelGGL(dkdv_kernel<64>, grid, block, 0, stream, a);
+  if (plan.pool_slots) {
+    const dim3 mg((unsigned)(plan.pool_slots / 2));
+    if (m.d == 128) hipLaunchKernelGGL(dkdv_merge_kernel<128>, mg, block, 0, stream, a);
+    else            hipLaunchKernelGGL(dkdv_merge_kernel<64>, mg, block, 0, stream, a);
+  }
   return hipGetLastError();
 }
 

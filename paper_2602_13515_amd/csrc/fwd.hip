@@ -24,7 +24,42 @@ struct FwdArgs {
   int H, N, Tm, Tn, chunk;
   int64_t sb, sh, sn;
   float scale_log2;     // scale * log2(e): softmax is evaluated with exp2
+  SplitPlan sp;         // long rows cut into parts (split.hip); sp.pool_slots == 0: every row is walked whole
 };
+
+// Partial result of one part of a split row, per thread of the workgroup: the unnormalised accumulator, then
+// the running maximum (log2 units) and the row sum, both already combined over the two halves of the wave.
+template <int D> constexpr int fwd_slot_floats() { return 256 * (D / 2) + 512; }
+size_t fwd_slot_bytes(const Dims& m) { return (size_t)(m.d == 128 ? fwd_slot_floats<128>() : fwd_slot_floats<64>()) * 4; }
+
+// O_i = diag(l)^-1 O (Alg. 1 step 18) -> bf16 (+ optional residual), LSE = m ln 2 + log l.
+template <int D>
+__device__ __forceinline__ void fwd_store_rows(const FwdArgs& a, int bh, int64_t base, int qrow, int hf,
+                                               const f32x16 (&oacc)[D / 32], float m_run, float l_tot) {
+  const float inv = 1.f / l_tot;
+  if (qrow < a.N) {
+    uint16_t* op = a.o + base + (int64_t)qrow * a.sn + 4 * hf;
+#pragma unroll
+    for (int mb = 0; mb < D / 32; ++mb)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        float x[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) x[e] = oacc[mb][4 * g + e] * inv;
+        const u32x2 pk2 = {pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3])};
+        *(u32x2*)(op + 32 * mb + 8 * g) = pk2;
+        if (a.o_res) {      // what the rounding to bf16 dropped, itself rounded to bf16
+          const float r0 = x[0] - __builtin_bit_cast(float, pk2[0] << 16);
+          const float r1 = x[1] - __builtin_bit_cast(float, pk2[0] & 0xffff0000u);
+          const float r2 = x[2] - __builtin_bit_cast(float, pk2[1] << 16);
+          const float r3 = x[3] - __builtin_bit_cast(float, pk2[1] & 0xffff0000u);
+          const u32x2 pr = {pack_bf16(r0, r1), pack_bf16(r2, r3)};
+          *(u32x2*)(a.o_res + (op - a.o) + 32 * mb + 8 * g) = pr;
+        }
+      }
+    if (hf == 0) a.lse[(int64_t)bh * a.N + qrow] = m_run * LN2 + __logf(l_tot);
+  }
+}
 
 template <int D>
 struct FwdCfg {
@@ -42,19 +77,36 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdArgs a) {
   __shared__ __align__(16) uint16_t Ks[2 * C::K_ELEMS];
   __shared__ __align__(16) uint16_t Vs[2 * C::V_ELEMS];
 
-  const HeadBlock hb = xcd_map(blockIdx.x, a.Tm, a.chunk);
-  if (!hb.valid) return;
-  const int bh = hb.bh;
-  // optional launch order: position hb.blk of this head's schedule -> query block (clamped: caller data)
-  const int i = a.row_order ? min(max(a.row_order[(int64_t)bh * a.Tm + hb.blk], 0), a.Tm - 1) : hb.blk;
+  // Which row, and which part of its list.  The first sp.pool_slots workgroups of the launch are the extra parts of
+  // split rows (part >= 1); the others take one row each: the whole list, or part 0 if the row is split.
+  int bh, i, part = 0, slot = -1;
+  if ((int)blockIdx.x < a.sp.pool_slots) {
+    if ((int)blockIdx.x >= a.sp.header[0]) return;
+    const int unit = a.sp.part_table[2 * blockIdx.x];
+    part = a.sp.part_table[2 * blockIdx.x + 1];
+    bh = unit / a.Tm; i = unit % a.Tm;
+    slot = a.sp.unit_slot[unit] + part;
+  } else {
+    const HeadBlock hb = xcd_map(blockIdx.x - a.sp.pool_slots, a.Tm, a.chunk);
+    if (!hb.valid) return;
+    bh = hb.bh;
+    // optional launch order: position hb.blk of this head's schedule -> query block (clamped: caller data)
+    i = a.row_order ? min(max(a.row_order[(int64_t)bh * a.Tm + hb.blk], 0), a.Tm - 1) : hb.blk;
+    if (a.sp.pool_slots) slot = a.sp.unit_slot[(int64_t)bh * a.Tm + i];
+  }
   const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int r32 = lane & 31, hf = lane >> 5;
   const int N = a.N;
   // counts and indices come from the caller's pattern: clamp them so that a corrupt list cannot
   // address memory outside the tensors
-  const int cnt = min(max(a.row_cnt[(int64_t)bh * a.Tm + i], 0), a.Tn);
+  int cnt = min(max(a.row_cnt[(int64_t)bh * a.Tm + i], 0), a.Tn);
   const int32_t* idx = a.row_idx + ((int64_t)bh * a.Tm + i) * a.Tn;
+  if (slot >= 0) {            // entries [part * S, (part + 1) * S) of the list (never empty: part < ceil(cnt / S))
+    const int S = a.sp.header[1];
+    idx += part * S;
+    cnt = min(cnt - part * S, S);
+  }
   const int qrow = i * BQ + w * 32 + r32;
 
   if (cnt == 0) {   // a row without any selected block (never produced by the masker): O = 0, LSE = -inf
@@ -294,36 +346,79 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdArgs a) {
     if (t + 1 < cnt) iteration(t + 1, stA, stB);  // tile t+2 (even) lives in set A
   }
 
-  // O_i = diag(l)^-1 O (step 18) and the log-sum-exp the backward pass needs
   const float l_tot = sum_halves(l_run);
-  const float inv = 1.f / l_tot;
-  if (qrow < N) {
-    uint16_t* op = a.o + base + (int64_t)qrow * a.sn + 4 * hf;
+  if (slot >= 0) {            // one part of a split row: leave the partial result to the merge kernel
+    float* ps = a.sp.pool + (int64_t)slot * a.sp.slot_floats;
+    f32x4* pa = (f32x4*)(ps + tid * (D / 2));
 #pragma unroll
     for (int mb = 0; mb < D / 32; ++mb)
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        float x[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) x[e] = oacc[mb][4 * g + e] * inv;
-        const u32x2 pk2 = {pack_bf16(x[0], x[1]), pack_bf16(x[2], x[3])};
-        *(u32x2*)(op + 32 * mb + 8 * g) = pk2;
-        if (a.o_res) {      // what the rounding to bf16 dropped, itself rounded to bf16
-          const float r0 = x[0] - __builtin_bit_cast(float, pk2[0] << 16);
-          const float r1 = x[1] - __builtin_bit_cast(float, pk2[0] & 0xffff0000u);
-          const float r2 = x[2] - __builtin_bit_cast(float, pk2[1] << 16);
-          const float r3 = x[3] - __builtin_bit_cast(float, pk2[1] & 0xffff0000u);
-          const u32x2 pr = {pack_bf16(r0, r1), pack_bf16(r2, r3)};
-          *(u32x2*)(a.o_res + (op - a.o) + 32 * mb + 8 * g) = pr;
-        }
-      }
-    if (hf == 0) a.lse[(int64_t)bh * N + qrow] = m_run * LN2 + __logf(l_tot);
+      for (int g = 0; g < 4; ++g)
+        pa[mb * 4 + g] = f32x4{oacc[mb][4 * g], oacc[mb][4 * g + 1], oacc[mb][4 * g + 2], oacc[mb][4 * g + 3]};
+    ps[256 * (D / 2) + tid] = m_run;
+    ps[256 * (D / 2) + 256 + tid] = l_tot;
+    return;
   }
+  // O_i = diag(l)^-1 O (step 18) and the log-sum-exp the backward pass needs
+  fwd_store_rows<D>(a, bh, base, qrow, hf, oacc, m_run, l_tot);
+}
+
+// Combines the parts of every split row, in part order (so the result does not depend on which part finished
+// first): m = max m_p, l = sum l_p 2^(m_p - m), O = sum O_p 2^(m_p - m) / l.  Same thread -> (row, channel) mapping
+// as fwd_kernel.  Workgroup x takes split row x of the plan; there are at most pool_slots / 2 of them.
+template <int D>
+__global__ __launch_bounds__(256) void fwd_merge_kernel(FwdArgs a) {
+  if ((int)blockIdx.x >= a.sp.header[2]) return;
+  const int unit = a.sp.merge_table[blockIdx.x];
+  const int bh = unit / a.Tm, i = unit % a.Tm;
+  const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int r32 = lane & 31, hf = lane >> 5;
+  const int cnt = min(max(a.row_cnt[unit], 0), a.Tn);
+  const int S = a.sp.header[1];
+  const int parts = (cnt + S - 1) / S;
+  const float* p0 = a.sp.pool + (int64_t)a.sp.unit_slot[unit] * a.sp.slot_floats;
+  float m = -INFINITY;
+  for (int p = 0; p < parts; p += 4) {       // four loads in flight per step
+    float mp[4];
+#pragma unroll
+    for (int x = 0; x < 4; ++x) mp[x] = p0[(int64_t)min(p + x, parts - 1) * a.sp.slot_floats + 256 * (D / 2) + tid];
+    m = fmaxf(fmaxf(m, fmaxf(mp[0], mp[1])), fmaxf(mp[2], mp[3]));
+  }
+  f32x16 oacc[D / 32];
+#pragma unroll
+  for (int mb = 0; mb < D / 32; ++mb)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) oacc[mb][v] = 0.f;
+  float l = 0.f;
+  // two parts per step: the loads of both are in flight together (the chain of parts is what takes the time)
+  for (int p = 0; p < parts; p += 2) {
+    const bool two = p + 1 < parts;
+    const float* ps0 = p0 + (int64_t)p * a.sp.slot_floats;
+    const float* ps1 = p0 + (int64_t)(two ? p + 1 : p) * a.sp.slot_floats;
+    const float sc0 = fast_exp2(ps0[256 * (D / 2) + tid] - m);
+    const float sc1 = two ? fast_exp2(ps1[256 * (D / 2) + tid] - m) : 0.f;
+    l = fmaf(ps0[256 * (D / 2) + 256 + tid], sc0, l);
+    l = fmaf(ps1[256 * (D / 2) + 256 + tid], sc1, l);
+    const f32x4* pa0 = (const f32x4*)(ps0 + tid * (D / 2));
+    const f32x4* pa1 = (const f32x4*)(ps1 + tid * (D / 2));
+    f32x4 x0[D / 8], x1[D / 8];
+#pragma unroll
+    for (int c = 0; c < D / 8; ++c) { x0[c] = pa0[c]; x1[c] = pa1[c]; }
+#pragma unroll
+    for (int mb = 0; mb < D / 32; ++mb)
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          oacc[mb][4 * g + e] = fmaf(x1[mb * 4 + g][e], sc1, fmaf(x0[mb * 4 + g][e], sc0, oacc[mb][4 * g + e]));
+  }
+  fwd_store_rows<D>(a, bh, base, i * BQ + w * 32 + r32, hf, oacc, m, l);
 }
 
 hipError_t launch_fwd(const void* q, const void* k, const void* v, const Dims& m, const int32_t* row_cnt,
                       const int32_t* row_idx, const int32_t* row_order, float scale, void* o, void* o_res,
-                      float* lse, hipStream_t stream) {
+                      float* lse, const SplitPlan& plan, hipStream_t stream) {
   FwdArgs a;
   a.q = (const uint16_t*)q; a.k = (const uint16_t*)k; a.v = (const uint16_t*)v;
   a.o = (uint16_t*)o; a.o_res = (uint16_t*)o_res; a.lse = lse;
@@ -332,9 +427,19 @@ hipError_t launch_fwd(const void* q, const void* k, const void* v, const Dims& m
   a.chunk = (m.Tm + 7) / 8;
   a.sb = m.sb; a.sh = m.sh; a.sn = m.sn;
   a.scale_log2 = scale * LOG2E;
-  const dim3 grid((unsigned)(m.B * m.H * 8 * a.chunk)), block(256);
+  a.sp = plan;
+  if (plan.pool_slots) {
+    const hipError_t e = launch_split_plan(row_cnt, (int64_t)m.B * m.H * m.Tm, m.Tn, SPLIT_MIN_PART, plan, stream);
+    if (e != hipSuccess) return e;
+  }
+  const dim3 grid((unsigned)(plan.pool_slots + m.B * m.H * 8 * a.chunk)), block(256);
   if (m.d == 128) hipLaunchKernelGGL(fwd_kernel<128>, grid, block, 0, stream, a);
   else            hipLaunchKernelGGL(fwd_kernel<64>, grid, block, 0, stream, a);
+  if (plan.pool_slots) {
+    const dim3 mg((unsigned)(plan.pool_slots / 2));
+    if (m.d == 128) hipLaunchKernelGGL(fwd_merge_kernel<128>, mg, block, 0, stream, a);
+    else            hipLaunchKernelGGL(fwd_merge_kernel<64>, mg, block, 0, stream, a);
+  }
   return hipGetLastError();
 }
 

@@ -39,20 +39,21 @@ int main(void) {
   spa2_shape toolong = shape(1, 4, SPA2_STATIC_MAX_ROWS / 4 + 64, 128, 128, 64, 0);
   size_t big = (size_t)1 << 40;
 
-  EXPECT(spa2_fwd(0, fake, fake, &ok, &full, 0.1f, fake, 0, (float*)fake, 0), SPA2_ERR_NULL);
-  EXPECT(spa2_fwd(fake, fake, fake, 0, &full, 0.1f, fake, 0, (float*)fake, 0), SPA2_ERR_NULL);
-  EXPECT(spa2_fwd(fake, fake, fake, &ok, &none, 0.1f, fake, 0, (float*)fake, 0), SPA2_ERR_NULL);
-  EXPECT(spa2_fwd(odd, fake, fake, &ok, &full, 0.1f, fake, 0, (float*)fake, 0), SPA2_ERR_ALIGN);
-  EXPECT(spa2_fwd(fake, fake, fake, &ok, &full, 0.0f, fake, 0, (float*)fake, 0), SPA2_ERR_RANGE);
-  EXPECT(spa2_fwd(fake, fake, fake, &ok, &full, NAN, fake, 0, (float*)fake, 0), SPA2_ERR_RANGE);
-  EXPECT(spa2_fwd(fake, fake, fake, &d96, &full, 0.1f, fake, 0, (float*)fake, 0), SPA2_ERR_UNSUPPORTED);
-  EXPECT(spa2_fwd(fake, fake, fake, &bq64, &full, 0.1f, fake, 0, (float*)fake, 0), SPA2_ERR_UNSUPPORTED);
-  EXPECT(spa2_fwd(fake, fake, fake, &n0, &full, 0.1f, fake, 0, (float*)fake, 0), SPA2_ERR_SHAPE);
-  EXPECT(spa2_fwd(fake, fake, fake, &sn132, &full, 0.1f, fake, 0, (float*)fake, 0), SPA2_ERR_ALIGN);
-  EXPECT(spa2_fwd(fake, fake, fake, &wide, &full, 0.1f, fake, 0, (float*)fake, 0), SPA2_ERR_SHAPE);
-  EXPECT(spa2_fwd(fake, fake, fake, &many, &full, 0.1f, fake, 0, (float*)fake, 0), SPA2_ERR_SHAPE);
-  EXPECT(spa2_fwd(fake, fake, fake, &huge, &full, 0.1f, fake, 0, (float*)fake, 0), SPA2_ERR_SHAPE);
+  EXPECT(spa2_fwd(0, fake, fake, &ok, &full, 0.1f, fake, 0, (float*)fake, 0, 0, 0), SPA2_ERR_NULL);
+  EXPECT(spa2_fwd(fake, fake, fake, 0, &full, 0.1f, fake, 0, (float*)fake, 0, 0, 0), SPA2_ERR_NULL);
+  EXPECT(spa2_fwd(fake, fake, fake, &ok, &none, 0.1f, fake, 0, (float*)fake, 0, 0, 0), SPA2_ERR_NULL);
+  EXPECT(spa2_fwd(odd, fake, fake, &ok, &full, 0.1f, fake, 0, (float*)fake, 0, 0, 0), SPA2_ERR_ALIGN);
+  EXPECT(spa2_fwd(fake, fake, fake, &ok, &full, 0.0f, fake, 0, (float*)fake, 0, 0, 0), SPA2_ERR_RANGE);
+  EXPECT(spa2_fwd(fake, fake, fake, &ok, &full, NAN, fake, 0, (float*)fake, 0, 0, 0), SPA2_ERR_RANGE);
+  EXPECT(spa2_fwd(fake, fake, fake, &d96, &full, 0.1f, fake, 0, (float*)fake, 0, 0, 0), SPA2_ERR_UNSUPPORTED);
+  EXPECT(spa2_fwd(fake, fake, fake, &bq64, &full, 0.1f, fake, 0, (float*)fake, 0, 0, 0), SPA2_ERR_UNSUPPORTED);
+  EXPECT(spa2_fwd(fake, fake, fake, &n0, &full, 0.1f, fake, 0, (float*)fake, 0, 0, 0), SPA2_ERR_SHAPE);
+  EXPECT(spa2_fwd(fake, fake, fake, &sn132, &full, 0.1f, fake, 0, (float*)fake, 0, 0, 0), SPA2_ERR_ALIGN);
+  EXPECT(spa2_fwd(fake, fake, fake, &wide, &full, 0.1f, fake, 0, (float*)fake, 0, 0, 0), SPA2_ERR_SHAPE);
+  EXPECT(spa2_fwd(fake, fake, fake, &many, &full, 0.1f, fake, 0, (float*)fake, 0, 0, 0), SPA2_ERR_SHAPE);
+  EXPECT(spa2_fwd(fake, fake, fake, &huge, &full, 0.1f, fake, 0, (float*)fake, 0, 0, 0), SPA2_ERR_SHAPE);
 
+  EXPECT(spa2_fwd(fake, fake, fake, &ok, &full, 0.1f, fake, 0, (float*)fake, odd, big, 0), SPA2_ERR_ALIGN);
   EXPECT(spa2_mask(fake, fake, &ok, 1, 0.5f, 0.1f, &full, 0, 0, big, 0), SPA2_ERR_WORKSPACE);
   EXPECT(spa2_mask(fake, fake, &ok, 1, 0.5f, 0.1f, &full, 0, fake, 16, 0), SPA2_ERR_WORKSPACE);
   EXPECT(spa2_mask(fake, fake, &ok, 0, 0.0f, 0.1f, &full, 0, fake, big, 0), SPA2_ERR_RANGE);
@@ -98,7 +99,9 @@ int main(void) {
     printf("spa2_topk_blocks\n"); ++failures;
   }
   if (spa2_mask_workspace_bytes(&huge) != 0 || spa2_bwd_workspace_bytes(&d96) != 0 || spa2_mask_workspace_bytes(0) != 0 ||
-      spa2_error_workspace_bytes(&n0) != 0 || spa2_mask_workspace_bytes(&ok) == 0 || spa2_bwd_workspace_bytes(&ok) == 0) {
+      spa2_error_workspace_bytes(&n0) != 0 || spa2_mask_workspace_bytes(&ok) == 0 || spa2_bwd_workspace_bytes(&ok) == 0 ||
+      spa2_fwd_workspace_bytes(&ok) == 0 || spa2_fwd_workspace_bytes(&d96) != 0 ||
+      spa2_bwd_workspace_min_bytes(&ok) == 0 || spa2_bwd_workspace_min_bytes(&ok) > spa2_bwd_workspace_bytes(&ok)) {
     printf("workspace sizes\n"); ++failures;
   }
   for (int c = 1; c >= -9; --c)

@@ -18,12 +18,17 @@ hipError_t launch_pattern_full(const Dims&, uint8_t*, int32_t*, int32_t*, int32_
   reached("launch_pattern_full");
 }
 hipError_t launch_fwd(const void*, const void*, const void*, const Dims&, const int32_t*, const int32_t*, const int32_t*,
-                      float, void*, void*, float*, hipStream_t) { reached("launch_fwd"); }
+                      float, void*, void*, float*, const SplitPlan&, hipStream_t) { reached("launch_fwd"); }
+size_t fwd_slot_bytes(const Dims& m) { return (size_t)(256 * (m.d / 2) + 512) * 4; }
+size_t dq_slot_bytes(const Dims& m) { return (size_t)256 * (m.d / 2) * 4; }
+size_t dkdv_slot_bytes(const Dims& m) { return (size_t)4 * (m.d / 32) * 16 * 64 * 4; }
 hipError_t launch_bwd_delta(const void*, const void*, const void*, const Dims&, float*, hipStream_t) { reached("launch_bwd_delta"); }
 hipError_t launch_bwd_dq(const void*, const void*, const void*, const void*, const float*, const float*, const Dims&,
-                         const int32_t*, const int32_t*, const int32_t*, float, void*, hipStream_t) { reached("launch_bwd_dq"); }
+                         const int32_t*, const int32_t*, const int32_t*, float, void*, const SplitPlan&, hipStream_t) {
+  reached("launch_bwd_dq");
+}
 hipError_t launch_bwd_dkdv(const void*, const void*, const void*, const void*, const float*, const float*, const Dims&,
-                           const int32_t*, const int32_t*, const int32_t*, float, void*, void*, hipStream_t) {
+                           const int32_t*, const int32_t*, const int32_t*, float, void*, void*, const SplitPlan&, hipStream_t) {
   reached("launch_bwd_dkdv");
 }
 size_t error_ws_bytes(const Dims& m) { return (size_t)m.B * m.H * 64; }

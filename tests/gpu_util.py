@@ -99,25 +99,28 @@ def gpu_mask(q, k, k_cnt, top_p, scale=None, want_pbar=True, columns=True):
     return pat, pbar
 
 
-def gpu_fwd(q, k, v, pat, scale=None, residual=False):
+def gpu_fwd(q, k, v, pat, scale=None, residual=False, split=True):
     B, H, N, d = q.shape
     scale = 1.0 / math.sqrt(d) if scale is None else scale
     g = Guarded()
     o = g.alloc(q.shape, q.dtype, q.device, float("nan"))
     o_res = g.alloc(q.shape, q.dtype, q.device, float("nan")) if residual else None
     lse = g.alloc((B, H, N), torch.float32, q.device, float("nan"))
-    spa2.spa2_fwd(q, k, v, pat, scale, o, lse, o_res)
+    # with the workspace, rows longer than the split length are walked by several workgroups
+    ws = g.alloc((spa2.spa2_fwd_workspace_bytes(q),), torch.uint8, q.device, 0) if split else None
+    spa2.spa2_fwd(q, k, v, pat, scale, o, lse, o_res, ws)
     torch.cuda.synchronize()
     g.check("spa2_fwd")
     return (o, lse, o_res) if residual else (o, lse)
 
 
-def gpu_bwd(q, k, v, o, do, lse, pat, scale=None, o_res=None):
+def gpu_bwd(q, k, v, o, do, lse, pat, scale=None, o_res=None, split=True):
     d = q.shape[-1]
     scale = 1.0 / math.sqrt(d) if scale is None else scale
     g = Guarded()
     dq, dk, dv = (g.alloc(q.shape, q.dtype, q.device, float("nan")) for _ in range(3))
-    ws = g.alloc((spa2.spa2_bwd_workspace_bytes(q),), torch.uint8, q.device, 0)
+    nbytes = spa2.spa2_bwd_workspace_bytes(q) if split else spa2.spa2_bwd_workspace_min_bytes(q)
+    ws = g.alloc((nbytes,), torch.uint8, q.device, 0)
     spa2.spa2_bwd(q, k, v, o, do, lse, pat, scale, dq, dk, dv, ws, o_res)
     torch.cuda.synchronize()
     g.check("spa2_bwd")

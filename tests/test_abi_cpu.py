@@ -63,18 +63,18 @@ def test_argument_validation_happens_on_the_host():
     odd = ctypes.c_void_p(0x1004)
     ok = _shape()
     f = lib.spa2_fwd
-    assert f(None, fake, fake, ctypes.byref(ok), ctypes.byref(pat), 0.1, fake, None, fake, None) == -1
-    assert f(fake, fake, fake, None, ctypes.byref(pat), 0.1, fake, None, fake, None) == -1
-    assert f(fake, fake, fake, ctypes.byref(ok), ctypes.byref(pat), 0.1, fake, None, fake, None) == -1   # empty pattern
+    assert f(None, fake, fake, ctypes.byref(ok), ctypes.byref(pat), 0.1, fake, None, fake, None, 0, None) == -1
+    assert f(fake, fake, fake, None, ctypes.byref(pat), 0.1, fake, None, fake, None, 0, None) == -1
+    assert f(fake, fake, fake, ctypes.byref(ok), ctypes.byref(pat), 0.1, fake, None, fake, None, 0, None) == -1   # empty pattern
     full = binding._Pattern(0x1000, 0x1000, 0x1000, 0x1000, 0x1000)
-    assert f(odd, fake, fake, ctypes.byref(ok), ctypes.byref(full), 0.1, fake, None, fake, None) == -4
-    assert f(fake, fake, fake, ctypes.byref(ok), ctypes.byref(full), 0.0, fake, None, fake, None) == -5
-    assert f(fake, fake, fake, ctypes.byref(_shape(d=96)), ctypes.byref(full), 0.1, fake, None, fake, None) == -3
-    assert f(fake, fake, fake, ctypes.byref(_shape(bq=64)), ctypes.byref(full), 0.1, fake, None, fake, None) == -3
-    assert f(fake, fake, fake, ctypes.byref(_shape(N=0)), ctypes.byref(full), 0.1, fake, None, fake, None) == -2
-    assert f(fake, fake, fake, ctypes.byref(_shape(sn=132)), ctypes.byref(full), 0.1, fake, None, fake, None) == -4
+    assert f(odd, fake, fake, ctypes.byref(ok), ctypes.byref(full), 0.1, fake, None, fake, None, 0, None) == -4
+    assert f(fake, fake, fake, ctypes.byref(ok), ctypes.byref(full), 0.0, fake, None, fake, None, 0, None) == -5
+    assert f(fake, fake, fake, ctypes.byref(_shape(d=96)), ctypes.byref(full), 0.1, fake, None, fake, None, 0, None) == -3
+    assert f(fake, fake, fake, ctypes.byref(_shape(bq=64)), ctypes.byref(full), 0.1, fake, None, fake, None, 0, None) == -3
+    assert f(fake, fake, fake, ctypes.byref(_shape(N=0)), ctypes.byref(full), 0.1, fake, None, fake, None, 0, None) == -2
+    assert f(fake, fake, fake, ctypes.byref(_shape(sn=132)), ctypes.byref(full), 0.1, fake, None, fake, None, 0, None) == -4
     wide = _shape(sn=(1 << 23) + 8, sh=1 << 40, sb=1 << 41)       # a tile's rows would not fit a 32-bit offset
-    assert f(fake, fake, fake, ctypes.byref(wide), ctypes.byref(full), 0.1, fake, None, fake, None) == -2
+    assert f(fake, fake, fake, ctypes.byref(wide), ctypes.byref(full), 0.1, fake, None, fake, None, 0, None) == -2
     m = lib.spa2_mask
     big = 1 << 30
     assert m(fake, fake, ctypes.byref(ok), 1, 0.5, 0.1, ctypes.byref(full), None, None, big, None) == -6
@@ -90,7 +90,7 @@ def test_argument_validation_happens_on_the_host():
     # B*H*(T_m + T_n) workgroups must fit a 32-bit grid: 2^24 heads of 20,000 tokens do not
     many = _shape(B=1 << 12, H=1 << 12, N=20000, d=64)
     assert lib.spa2_mask_columns(ctypes.byref(many), ctypes.byref(full), None) == -2
-    assert f(fake, fake, fake, ctypes.byref(many), ctypes.byref(full), 0.1, fake, None, fake, None) == -2
+    assert f(fake, fake, fake, ctypes.byref(many), ctypes.byref(full), 0.1, fake, None, fake, None, 0, None) == -2
     # the workspace-free backward: same checks, and its fixed array bounds B*H*N
     bs = lib.spa2_bwd_static
     sargs = [fake, fake, fake, fake, None, fake, fake]
@@ -232,8 +232,9 @@ def test_argument_checks_under_host_sanitizers():
             [clang, "-std=c99", "-g", "-c", *san, *inc, os.path.join(here, "driver.c"), "-o", o("driver.o")],
             [hipcc, *dev, *xsan, *inc, "-c", os.path.join(ROOT, "paper_2602_13515_amd", "csrc", "api.hip"), "-o", o("api.o")],
             [hipcc, *dev, *xsan, *inc, "-x", "hip", "-c", os.path.join(here, "launch_stubs.cpp"), "-o", o("stubs.o")],
+        [hipcc, *dev, *xsan, *inc, "-c", os.path.join(ROOT, "paper_2602_13515_amd", "csrc", "split.hip"), "-o", o("split.o")],
             [hipcc, "--offload-arch=gfx950", "-fsanitize=address", "-fsanitize=undefined", "-fno-gpu-sanitize",
-             o("api.o"), o("stubs.o"), o("driver.o"), "-o", o("abi_check")],
+             o("api.o"), o("stubs.o"), o("split.o"), o("driver.o"), "-o", o("abi_check")],
         ]
         for cmd in steps:
             r = subprocess.run(cmd, capture_output=True, text=True)

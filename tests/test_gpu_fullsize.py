@@ -34,7 +34,8 @@ def _run_path(w, q, k, v, do, k_frac=None, top_p=None, want_pbar=True):
     spa2.spa2_mask_pool(q, k, ws_m)
     spa2.spa2_mask_select(q, k_cnt, top_p, scale, pat, pbar, ws_m)
     spa2.spa2_mask_columns(q, pat)
-    spa2.spa2_fwd(q, k, v, pat, scale, o, lse, o_res)
+    ws_f = g.alloc((spa2.spa2_fwd_workspace_bytes(q),), torch.uint8, q.device, 0)
+    spa2.spa2_fwd(q, k, v, pat, scale, o, lse, o_res, ws_f)
     dq = dk = dv = None
     if do is not None:
         dq, dk, dv = (g.alloc(q.shape, q.dtype, q.device, nan) for _ in range(3))

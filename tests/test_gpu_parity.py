@@ -324,3 +324,48 @@ def test_whole_step_replays_from_a_hip_graph():
         torch.cuda.synchronize()
         for name, got, ref in zip(("mask", "O", "LSE", "dQ", "dK", "dV"), (pat.mask, o, lse, dq, dk, dv), eager):
             assert torch.equal(got, ref), (rep, name)
+
+
+def test_long_rows_and_columns_are_split_and_merged():
+    """A small layer whose longest rows and columns are several times the split length (Top-p-bound rows of the
+    low-rank recipe, hot key blocks): with the workspaces, lists longer than S = max(16, tiles / 2048) are walked by
+    several workgroups and merged in part order (Alg. 1 step 18: the final division makes the merge of (O, m, l)
+    exact up to rounding).  Results must match the oracle to the same bars as the unsplit path, agree with the
+    unsplit path to rounding, and be bit-identical from run to run."""
+    w = _small("split", 9000, 128, kind="lowrank", H=2, k=0.05, p=0.8)          # T_m = 71, T_n = 141
+    q, k, v, do = wl.make_inputs(w, seed=21)
+    qd, kd, vd, dod = (t.to(dev()) for t in (q, k, v, do))
+    k_cnt = spa2.spa2_topk_blocks(w.k_frac, w.Tn)
+    pat, _ = gpu_mask(qd, kd, k_cnt, w.top_p, want_pbar=False)
+    mask = check_pattern_consistency(pat)
+    rc, cc = mask.sum(-1), mask.sum(-2)
+    tiles = int(mask.sum())
+    S_rows, S_cols = max(16, -(-tiles // 2048)), max(8, -(-tiles // 2048))
+    print(f"tiles {tiles}; longest row {rc.max()} (split length {S_rows}), longest column {cc.max()} (split length {S_cols}); "
+          f"rows split {(rc > S_rows).sum()}, columns split {(cc > S_cols).sum()}", flush=True)
+    assert rc.max() > 3 * S_rows and cc.max() > 3 * S_cols, "the case must exercise several parts per list"
+    runs = []
+    for split in (True, True, False):
+        o, lse, o_res = gpu_fwd(qd, kd, vd, pat, residual=True, split=split)
+        dq, dk, dv = gpu_bwd(qd, kd, vd, o, dod, lse, pat, o_res=o_res, split=split)
+        runs.append((o, lse, o_res, dq, dk, dv))
+    for a, b in zip(runs[0], runs[1]):
+        assert torch.equal(a, b), "split results must not depend on the order in which parts finish"
+    r_dq, r_dk, r_dv, r_o, r_lse = orc.attention_bwd_bh(f64(q), f64(k), f64(v), mask, f64(do))
+    for tag, (o, lse, o_res, dq, dk, dv) in (("split", runs[0]), ("whole", runs[2])):
+        print(tag, "O", assert_close("O", f64(o), r_o))
+        assert np.abs(f64(lse) - r_lse).max() <= 2e-3
+        print(tag, "dQ", assert_close("dQ", f64(dq), r_dq, max_abs=LOWRANK_MAX_ABS))
+        print(tag, "dK", assert_close("dK", f64(dk), r_dk, max_abs=LOWRANK_MAX_ABS))
+        print(tag, "dV", assert_close("dV", f64(dv), r_dv))
+    # The two paths differ by rounding only (another summation order; partial results stay fp32): stored bf16
+    # values two spacings apart at most.  The forward outputs are compared directly (LSE: the row sum is taken over
+    # P rounded against each part's own running maximum); the gradients are compared on the SAME forward outputs.
+    o, lse, o_res = runs[0][:3]
+    whole = gpu_bwd(qd, kd, vd, o, dod, lse, pat, o_res=o_res, split=False)
+    pairs = [("O", runs[0][0], runs[2][0]), ("LSE", runs[0][1], runs[2][1])] + \
+            [(n, a, b) for n, a, b in zip(("dQ", "dK", "dV"), runs[0][3:], whole)]
+    for name, a, b in pairs:
+        d = (a.float() - b.float()).abs()
+        bound = 2.0 ** -6 * b.float().abs() + 1e-3 if name != "LSE" else torch.full_like(d, 1e-3)
+        assert bool((d <= bound).all()), (name, float(d.max()))

@@ -20,7 +20,8 @@ def _both_ways(w, seed):
     scale = 1.0 / math.sqrt(w.d)
     pat, _ = gpu_mask(q, k, spa2.spa2_topk_blocks(w.k_frac, w.Tn), w.top_p, want_pbar=False)
     o, lse, o_res = gpu_fwd(q, k, v, pat, residual=True)
-    ref = gpu_bwd(q, k, v, o, do, lse, pat, o_res=o_res)
+    # (the mandatory part of the workspace only, as the static path has: no list is split on either side)
+    ref = gpu_bwd(q, k, v, o, do, lse, pat, o_res=o_res, split=False)
     got = tuple(torch.full_like(q, float("nan")) for _ in range(3))
     spa2.spa2_bwd_static(q, k, v, o, do, lse, pat, scale, *got, o_res=o_res)
     torch.cuda.synchronize()
