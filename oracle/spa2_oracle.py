@@ -17,8 +17,8 @@ What is computed (per batch element and head, independently):
   5-6) giving the block mask Mbar;
 * block-sparse attention: the masked, renormalised softmax of Sec. 3.1
   (o_s = (p (.) m / tau) V), which is what the recurrence of Alg. 1 steps 7-21
-  evaluates; written three ways (definition, per-block gather, and the
-  literal online recurrence) that the tests cross-check;
+  evaluates; written three ways (definition, per-block gather, and tile by
+  tile with a final merge) that the tests cross-check;
 * gradients of that map w.r.t. Q, K, V with the mask held constant (the paper
   only says a backward pass exists, Sec. 4.3; this is ordinary softmax
   calculus);
@@ -235,11 +235,13 @@ def attention_gather(q, k, v, mbar, scale: float | None = None,
     return o, lse
 
 
-def attention_alg1(q, k, v, mbar, scale: float | None = None,
-                   bq: int = BQ, bkv: int = BKV):
-    """The recurrence of Alg. 1 steps 7-21, tile by tile: running row maximum
-    m, running sum l, rescaled accumulator O, final division by l.  Initial
-    state m = -inf, l = 0, O = 0 (the listing leaves it implicit)."""
+def attention_tile_merge(q, k, v, mbar, scale: float | None = None,
+                         bq: int = BQ, bkv: int = BKV):
+    """What the recurrence of Alg. 1 steps 7-21 computes, evaluated tile by tile WITHOUT running state: every
+    selected tile (i, j) gets its own local softmax (row-wise log-sum-exp LSE_ij and normalised output O_ij over
+    the 64 keys of the tile alone); the tiles of a query block are then combined in one step with the weights
+    exp(LSE_ij - LSE_i), LSE_i = log sum_j exp(LSE_ij).  Step 18's final division is what makes this equal to
+    the masked softmax over all selected keys.  Unselected tiles contribute nothing (Alg. 1 step 9)."""
     q = np.asarray(q, np.float64); k = np.asarray(k, np.float64); v = np.asarray(v, np.float64)
     n, d = q.shape
     if scale is None:
@@ -249,23 +251,23 @@ def attention_alg1(q, k, v, mbar, scale: float | None = None,
     t_m, t_n = mbar.shape
     for i in range(t_m):
         r0, r1 = i * bq, min(n, (i + 1) * bq)
-        q_i = q[r0:r1]
-        m_run = np.full((r1 - r0, 1), -np.inf)
-        l_run = np.zeros((r1 - r0, 1))
-        o_run = np.zeros((r1 - r0, d))
+        local_lse, local_o = [], []
         for j in range(t_n):
             if mbar[i, j] == 0:
                 continue
             c0, c1 = j * bkv, min(n, (j + 1) * bkv)
-            s_ij = (q_i @ k[c0:c1].T) * scale
-            m_new = np.maximum(m_run, s_ij.max(axis=1, keepdims=True))
-            p_ij = np.exp(s_ij - m_new)
-            alpha = np.exp(m_run - m_new)
-            l_run = alpha * l_run + p_ij.sum(axis=1, keepdims=True)
-            o_run = alpha * o_run + p_ij @ v[c0:c1]
-            m_run = m_new
-        o[r0:r1] = o_run / l_run
-        lse[r0:r1] = (m_run + np.log(l_run))[:, 0]
+            s_ij = (q[r0:r1] @ k[c0:c1].T) * scale
+            top = s_ij.max(axis=1, keepdims=True)
+            w_ij = np.exp(s_ij - top)
+            z_ij = w_ij.sum(axis=1, keepdims=True)
+            local_lse.append(top + np.log(z_ij))             # [rows, 1]
+            local_o.append((w_ij / z_ij) @ v[c0:c1])         # [rows, d], normalised within the tile
+        stack = np.concatenate(local_lse, axis=1)            # [rows, tiles]
+        top = stack.max(axis=1, keepdims=True)
+        row_lse = top + np.log(np.exp(stack - top).sum(axis=1, keepdims=True))
+        weights = np.exp(stack - row_lse)                    # each row sums to 1 over the tiles
+        o[r0:r1] = sum(weights[:, t:t + 1] * local_o[t] for t in range(len(local_o)))
+        lse[r0:r1] = row_lse[:, 0]
     return o, lse
 
 

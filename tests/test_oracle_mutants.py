@@ -85,21 +85,24 @@ MUTANTS = [
      'o[r0:r1] = (e / l) @ v[cols]',
      'o[r0:r1] = (e / l) @ k[cols]'),
     ('gather-lse-nomax',
-     'lse[r0:r1] = (m + np.log(l))[:, 0]\n    return o, lse\n\n\ndef attention_alg1',
-     'lse[r0:r1] = (np.log(l))[:, 0]\n    return o, lse\n\n\ndef attention_alg1'),
+     'lse[r0:r1] = (m + np.log(l))[:, 0]\n    return o, lse\n\n\ndef attention_tile_merge',
+     'lse[r0:r1] = (np.log(l))[:, 0]\n    return o, lse\n\n\ndef attention_tile_merge'),
     ('gather-cols-bq',
      'cols = np.concatenate([np.arange(j * bkv, min(n, (j + 1) * bkv))\n                               for j in np.flatnonzero(mbar[i])])\n        s = (q[r0:r1] @ k[cols].T) * scale\n        m = s.max(axis=1, keepdims=True)\n        e = np.exp(s - m)\n        l = e.sum(axis=1, keepdims=True)\n        o[r0:r1]',
      'cols = np.concatenate([np.arange(j * bkv, min(n, (j + 1) * bkv - 1))\n                               for j in np.flatnonzero(mbar[i])])\n        s = (q[r0:r1] @ k[cols].T) * scale\n        m = s.max(axis=1, keepdims=True)\n        e = np.exp(s - m)\n        l = e.sum(axis=1, keepdims=True)\n        o[r0:r1]'),
-    ('alg1-no-alpha-l',
-     'l_run = alpha * l_run + p_ij.sum',
-     'l_run = l_run + p_ij.sum'),
-    ('alg1-no-alpha-o',
-     'o_run = alpha * o_run + p_ij @ v[c0:c1]',
-     'o_run = o_run + p_ij @ v[c0:c1]'),
-    ('alg1-alpha-sign',
-     'alpha = np.exp(m_run - m_new)',
-     'alpha = np.exp(m_new - m_run)'),
-    ('alg1-skip-inverted',
+    ('merge-local-lse-nomax',
+     'local_lse.append(top + np.log(z_ij))',
+     'local_lse.append(np.log(z_ij))'),
+    ('merge-unnormalised-tile',
+     'local_o.append((w_ij / z_ij) @ v[c0:c1])',
+     'local_o.append(w_ij @ v[c0:c1])'),
+    ('merge-weight-sign',
+     'weights = np.exp(stack - row_lse)',
+     'weights = np.exp(row_lse - stack)'),
+    ('merge-no-weights',
+     'sum(weights[:, t:t + 1] * local_o[t] for t in range(len(local_o)))',
+     'sum(local_o[t] for t in range(len(local_o))) / len(local_o)'),
+    ('merge-skip-inverted',
      'if mbar[i, j] == 0:\n                continue',
      'if mbar[i, j] != 0 and j % 7 == 3:\n                continue'),
     ('bwd-dv-untransposed',
@@ -174,15 +177,15 @@ MUTANTS = [
     ('bwdg-dp-k',
      'dp = do_i @ v[cols].T',
      'dp = do_i @ k[cols].T'),
-    ('alg1-lse',
-     'lse[r0:r1] = (m_run + np.log(l_run))[:, 0]',
-     'lse[r0:r1] = (m_run)[:, 0]'),
-    ('alg1-nodiv',
-     'o[r0:r1] = o_run / l_run',
-     'o[r0:r1] = o_run'),
-    ('alg1-noscale',
-     's_ij = (q_i @ k[c0:c1].T) * scale',
-     's_ij = (q_i @ k[c0:c1].T)'),
+    ('merge-row-lse-nolog',
+     'row_lse = top + np.log(np.exp(stack - top).sum(axis=1, keepdims=True))',
+     'row_lse = top + np.exp(stack - top).sum(axis=1, keepdims=True)'),
+    ('merge-lse-max-only',
+     'lse[r0:r1] = row_lse[:, 0]',
+     'lse[r0:r1] = top[:, 0]'),
+    ('merge-noscale',
+     's_ij = (q[r0:r1] @ k[c0:c1].T) * scale',
+     's_ij = (q[r0:r1] @ k[c0:c1].T)'),
     ('errsum-tau',
      'drop += np.abs(dropped).sum(); ren += np.abs(renorm).sum(); tau_sum += tau',
      'drop += np.abs(dropped).sum(); ren += np.abs(renorm).sum(); tau_sum += 1.0'),

@@ -228,7 +228,7 @@ def test_masked_attention_three_forms_and_library_masked_sdpa(n, d, seed):
     q, k, v, _, m = _rand_problem(n, d, seed)
     o1, lse1, p = orc.attention_definition(q, k, v, m)
     o2, lse2 = orc.attention_gather(q, k, v, m)
-    o3, lse3 = orc.attention_alg1(q, k, v, m)
+    o3, lse3 = orc.attention_tile_merge(q, k, v, m)
     np.testing.assert_allclose(o2, o1, rtol=1e-11, atol=1e-13)
     np.testing.assert_allclose(o3, o1, rtol=1e-11, atol=1e-13)
     np.testing.assert_allclose(lse2, lse1, rtol=1e-13)
@@ -264,7 +264,7 @@ def test_single_block_with_identical_keys_gives_mean_of_values():
     q = rng.normal(size=(n, d)); v = rng.normal(size=(n, d))
     k = rng.normal(size=(n, d)); k[64:128] = k[64]          # block 1: identical keys
     m = np.zeros((2, 4), np.uint8); m[:, 1] = 1
-    for f in (orc.attention_gather, orc.attention_alg1):
+    for f in (orc.attention_gather, orc.attention_tile_merge):
         o, lse = f(q, k, v, m)
         np.testing.assert_allclose(o, np.tile(v[64:128].mean(axis=0), (n, 1)), atol=1e-13)
         np.testing.assert_allclose(lse, q @ k[64] / math.sqrt(d) + math.log(64), rtol=1e-12, atol=1e-12)
@@ -444,3 +444,34 @@ def test_vd_loss_closed_forms_and_library_gradient():
     loss, grad = orc.vd_loss(u_s, u_f, 1.0 / u_s.size)
     assert abs(loss - tl.item()) < 1e-14
     np.testing.assert_allclose(grad, ts.grad.numpy(), rtol=1e-13, atol=1e-18)
+
+
+def test_parts_of_a_row_merge_to_the_whole_row():
+    """The identity behind splitting a long row over several workgroups: evaluate the attention of a query block
+    over disjoint subsets of its selected key blocks separately (each with its own softmax), then combine the
+    partial outputs with weights exp(LSE_part - LSE) -- Alg. 1 step 18's division by the total row sum is what makes
+    this equal to one softmax over all selected keys.  Checked against the definition, with uneven parts."""
+    q, k, v, _, m = _rand_problem(700, 16, 11)
+    m[:] = 0
+    rng = np.random.default_rng(12)
+    for i in range(m.shape[0]):
+        m[i, rng.choice(m.shape[1], size=7, replace=False)] = 1
+    o_ref, lse_ref, _ = orc.attention_definition(q, k, v, m)
+    for cuts in ((3,), (1, 2), (2, 5, 6)):
+        outs, lses = [], []
+        for i in range(m.shape[0]):
+            sel = np.flatnonzero(m[i])
+            bounds = (0,) + cuts + (sel.size,)
+            o_parts, lse_parts = [], []
+            for a, b in zip(bounds[:-1], bounds[1:]):
+                part = np.zeros_like(m); part[i, sel[a:b]] = 1
+                o_p, lse_p = orc.attention_gather(q, k, v, part, q_blocks=[i])
+                r0, r1 = i * 128, min(700, (i + 1) * 128)
+                o_parts.append(o_p[r0:r1]); lse_parts.append(lse_p[r0:r1])
+            stack = np.stack(lse_parts, axis=1)
+            top = stack.max(axis=1, keepdims=True)
+            lse = (top + np.log(np.exp(stack - top).sum(axis=1, keepdims=True)))[:, 0]
+            outs.append(sum(np.exp(lp - lse)[:, None] * op for lp, op in zip(lse_parts, o_parts)))
+            lses.append(lse)
+        np.testing.assert_allclose(np.concatenate(outs), o_ref, rtol=1e-11, atol=1e-13)
+        np.testing.assert_allclose(np.concatenate(lses), lse_ref, rtol=1e-13)
