@@ -295,13 +295,14 @@ def test_whole_step_replays_from_a_hip_graph():
     pat = spa2.alloc_pattern(w.B, w.H, w.N, dev())
     ws_m = torch.empty(spa2.spa2_mask_workspace_bytes(q), dtype=torch.uint8, device=dev())
     ws_b = torch.empty(spa2.spa2_bwd_workspace_bytes(q), dtype=torch.uint8, device=dev())
+    ws_f = torch.empty(spa2.spa2_fwd_workspace_bytes(q), dtype=torch.uint8, device=dev())   # long rows are split
     o = torch.empty_like(q); o_res = torch.empty_like(q)
     lse = torch.empty((w.B, w.H, w.N), dtype=torch.float32, device=dev())
     dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
 
     def step():
         spa2.spa2_mask(q, k, k_cnt, w.top_p, scale, pat, None, ws_m)
-        spa2.spa2_fwd(q, k, v, pat, scale, o, lse, o_res)
+        spa2.spa2_fwd(q, k, v, pat, scale, o, lse, o_res, ws_f)
         spa2.spa2_bwd(q, k, v, o, do, lse, pat, scale, dq, dk, dv, ws_b, o_res)
 
     step()
@@ -317,8 +318,8 @@ def test_whole_step_replays_from_a_hip_graph():
             step()
     torch.cuda.synchronize()
     for rep in range(3):
-        for t in (pat.mask, o, lse, dq, dk, dv):
-            t.zero_()                            # eager work between the replays
+        for t in (pat.mask, o, lse, dq, dk, dv, ws_f, ws_b):
+            t.zero_()                            # eager work between the replays (plans and partial sums too)
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
