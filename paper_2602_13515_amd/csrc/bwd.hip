@@ -324,9 +324,8 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(DqArgs a) {
 // Adds the parts of every split row in part order (fixed order: deterministic).  Same thread -> (row, channel)
 // mapping as dq_kernel; workgroup x takes split row x of the plan.
 template <int D>
-__global__ __launch_bounds__(256) void dq_merge_kernel(DqArgs a) {
-  if ((int)blockIdx.x >= a.sp.header[2]) return;
-  const int unit = a.sp.merge_table[blockIdx.x];
+__device__ __forceinline__ void dq_merge_kernel_one(const DqArgs& a, int m_idx) {
+  const int unit = a.sp.merge_table[m_idx];
   const int bh = unit / a.Tm, i = unit % a.Tm;
   const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -358,6 +357,13 @@ __global__ __launch_bounds__(256) void dq_merge_kernel(DqArgs a) {
         }
   }
   dq_store_rows<D>(a, base, i * BQ + w * 32 + (lane & 31), lane >> 5, acc);
+}
+
+// (one workgroup per split list as a rule; the loop covers a launch with fewer workgroups than lists)
+template <int D>
+__global__ __launch_bounds__(256) void dq_merge_kernel(DqArgs a) {
+  const int n = a.sp.header[2];
+  for (int m_idx = blockIdx.x; m_idx < n; m_idx += gridDim.x) dq_merge_kernel_one<D>(a, m_idx);
 }
 
 hipError_t launch_bwd_dq(const void* q, const void* k, const void* v, const void* d_o, const float* lse,

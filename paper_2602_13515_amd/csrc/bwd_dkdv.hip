@@ -397,10 +397,9 @@ void dkdv_kernel(DkvArgs a) {
 // Adds the parts of every split column in part order (fixed order: deterministic) and stores dK, dV.  Same thread
 // -> (key, channel) mapping as the end of dkdv_kernel; workgroup x takes split column x of the plan.
 template <int D>
-__global__ __launch_bounds__(128) void dkdv_merge_kernel(DkvArgs a) {
+__device__ __forceinline__ void dkdv_merge_kernel_one(const DkvArgs& a, int m_idx) {
   constexpr int NMB = D / 32;
-  if ((int)blockIdx.x >= a.sp.header[2]) return;
-  const int unit = a.sp.merge_table[blockIdx.x];
+  const int unit = a.sp.merge_table[m_idx];
   const int bh = unit / a.Tn, j = unit % a.Tn;
   const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, r32 = lane & 31, hf = lane >> 5;
@@ -437,6 +436,13 @@ __global__ __launch_bounds__(128) void dkdv_merge_kernel(DkvArgs a) {
       }
     }
   }
+}
+
+// (one workgroup per split list as a rule; the loop covers a launch with fewer workgroups than lists)
+template <int D>
+__global__ __launch_bounds__(128) void dkdv_merge_kernel(DkvArgs a) {
+  const int n = a.sp.header[2];
+  for (int m_idx = blockIdx.x; m_idx < n; m_idx += gridDim.x) dkdv_merge_kernel_one<D>(a, m_idx);
 }
 
 hipError_t launch_bwd_dkdv(const void* q, const void* k, const void* v, const void* d_o, const float* lse,

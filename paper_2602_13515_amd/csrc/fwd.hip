@@ -367,9 +367,8 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(FwdArgs a) {
 // first): m = max m_p, l = sum l_p 2^(m_p - m), O = sum O_p 2^(m_p - m) / l.  Same thread -> (row, channel) mapping
 // as fwd_kernel.  Workgroup x takes split row x of the plan; there are at most pool_slots / 2 of them.
 template <int D>
-__global__ __launch_bounds__(256) void fwd_merge_kernel(FwdArgs a) {
-  if ((int)blockIdx.x >= a.sp.header[2]) return;
-  const int unit = a.sp.merge_table[blockIdx.x];
+__device__ __forceinline__ void fwd_merge_kernel_one(const FwdArgs& a, int m_idx) {
+  const int unit = a.sp.merge_table[m_idx];
   const int bh = unit / a.Tm, i = unit % a.Tm;
   const int64_t base = (int64_t)(bh / a.H) * a.sb + (int64_t)(bh % a.H) * a.sh;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -414,6 +413,13 @@ __global__ __launch_bounds__(256) void fwd_merge_kernel(FwdArgs a) {
           oacc[mb][4 * g + e] = fmaf(x1[mb * 4 + g][e], sc1, fmaf(x0[mb * 4 + g][e], sc0, oacc[mb][4 * g + e]));
   }
   fwd_store_rows<D>(a, bh, base, i * BQ + w * 32 + r32, hf, oacc, m, l);
+}
+
+// (one workgroup per split list as a rule; the loop covers a launch with fewer workgroups than lists)
+template <int D>
+__global__ __launch_bounds__(256) void fwd_merge_kernel(FwdArgs a) {
+  const int n = a.sp.header[2];
+  for (int m_idx = blockIdx.x; m_idx < n; m_idx += gridDim.x) fwd_merge_kernel_one<D>(a, m_idx);
 }
 
 hipError_t launch_fwd(const void* q, const void* k, const void* v, const Dims& m, const int32_t* row_cnt,

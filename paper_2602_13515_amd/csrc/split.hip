@@ -71,20 +71,29 @@ __device__ __forceinline__ int wave_incl_scan(int x, int lane) {
 __global__ __launch_bounds__(1024) void split_plan_kernel(const int32_t* cnt, int units, int cnt_max, int pool,
                                                           int min_part, int32_t* header, int32_t* unit_slot,
                                                           int32_t* part_table, int32_t* merge_table) {
-  constexpr int UPT = 4;                                   // consecutive units per thread and tile
+  constexpr int UPT = 8;                                   // consecutive units per thread and tile (two 16-byte loads)
   __shared__ unsigned long long tot_s[16];
   __shared__ int wsum[3][16];
   __shared__ int n_extra_s, n_split_s;
   const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
   if (t == 0) { n_extra_s = 0; n_split_s = 0; }
-  auto load4 = [&](int u, int (&c)[UPT]) {                 // lengths of units u .. u+3 (0 past the end), clamped
+  const bool vec_ok = ((uintptr_t)cnt & 15) == 0;
+  auto load4 = [&](int u, int (&c)[UPT]) {                 // lengths of units u .. u+UPT-1 (0 past the end), clamped
+    if (vec_ok && u + UPT <= units) {
+      typedef __attribute__((ext_vector_type(4))) int i32x4;
+      const i32x4 a = *(const i32x4*)(cnt + u), b = *(const i32x4*)(cnt + u + 4);
 #pragma unroll
-    for (int x = 0; x < UPT; ++x) c[x] = u + x < units ? min(max(cnt[u + x], 0), cnt_max) : 0;
+      for (int x = 0; x < 4; ++x) { c[x] = min(max(a[x], 0), cnt_max); c[4 + x] = min(max(b[x], 0), cnt_max); }
+    } else {
+#pragma unroll
+      for (int x = 0; x < UPT; ++x) c[x] = u + x < units ? min(max(cnt[u + x], 0), cnt_max) : 0;
+    }
   };
   unsigned long long mine = 0;
   for (int u = UPT * t; u < units; u += UPT * 1024) {
     int c[UPT]; load4(u, c);
-    mine += (unsigned long long)(c[0] + c[1]) + (unsigned long long)(c[2] + c[3]);
+#pragma unroll
+    for (int x = 0; x < UPT; ++x) mine += (unsigned long long)c[x];
   }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) mine += __shfl_xor(mine, off, 64);
