@@ -414,17 +414,18 @@ hipError_t launch_select(const float* qbar, const float* kbar, const Dims& m, in
 }
 
 // ------------------------------------------------------------------ column lists
-// One workgroup lists 64 key blocks of one head: thread (seg, c) walks a quarter of the query blocks of
-// column c twice, first counting, then (after the four counts of the column have been exchanged through
-// LDS) writing its ascending piece of the list at the right offset.
-__global__ __launch_bounds__(256) void columns_kernel(const uint8_t* mask, int Tm, int Tn, int32_t* col_cnt,
-                                                      int32_t* col_idx) {
-  __shared__ int seg_cnt[4][64];
+// One workgroup lists 64 key blocks of one head: thread (seg, c) walks one of COL_SEGS runs of query blocks of
+// column c twice, first counting, then (after the counts of the column's runs have been exchanged through LDS)
+// writing its ascending piece of the list at the right offset.
+constexpr int COL_SEGS = 16;
+__global__ __launch_bounds__(64 * COL_SEGS) void columns_kernel(const uint8_t* mask, int Tm, int Tn, int32_t* col_cnt,
+                                                                int32_t* col_idx) {
+  __shared__ int seg_cnt[COL_SEGS][64];
   const int bh = blockIdx.y;
   const int c = threadIdx.x & 63, seg = threadIdx.x >> 6;
   const int j = blockIdx.x * 64 + c;
-  const int per = (Tm + 3) / 4;
-  const int i0 = seg * per, i1 = min(Tm, i0 + per);
+  const int per = (Tm + COL_SEGS - 1) / COL_SEGS;
+  const int i0 = min(Tm, seg * per), i1 = min(Tm, i0 + per);
   const bool live = j < Tn;
   const uint8_t* mp = mask + (int64_t)bh * Tm * Tn + (live ? j : 0);
   int n = 0;
@@ -438,7 +439,7 @@ __global__ __launch_bounds__(256) void columns_kernel(const uint8_t* mask, int T
   int32_t* out = col_idx + ((int64_t)bh * Tn + j) * Tm;
   for (int i = i0; i < i1; ++i)
     if (mp[(int64_t)i * Tn]) out[at++] = i;
-  if (seg == 3) col_cnt[(int64_t)bh * Tn + j] = at;
+  if (seg == COL_SEGS - 1) col_cnt[(int64_t)bh * Tn + j] = at;
 }
 
 // Launch order of the key blocks of one head for the dK/dV kernel: longest column first, dealt round-robin
@@ -476,7 +477,7 @@ __global__ __launch_bounds__(256) void col_order_kernel(const int32_t* col_cnt, 
 hipError_t launch_columns(const uint8_t* mask, const Dims& m, int32_t* col_cnt, int32_t* col_idx,
                           int32_t* col_order, hipStream_t stream) {
   const dim3 grid((unsigned)((m.Tn + 63) / 64), (unsigned)(m.B * m.H)), block(256);
-  hipLaunchKernelGGL(columns_kernel, grid, block, 0, stream, mask, m.Tm, m.Tn, col_cnt, col_idx);
+  hipLaunchKernelGGL(columns_kernel, grid, dim3(64 * COL_SEGS), 0, stream, mask, m.Tm, m.Tn, col_cnt, col_idx);
   if (col_order) {
     const dim3 g2((unsigned)(m.B * m.H));
     if (m.Tn <= 512)       hipLaunchKernelGGL(col_order_kernel<512>, g2, block, 0, stream, col_cnt, m.Tn, col_order);
