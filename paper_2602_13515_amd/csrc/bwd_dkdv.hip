@@ -49,12 +49,6 @@ size_t dkdv_slot_bytes(const Dims& m) { return (size_t)(m.d == 128 ? dkdv_slot_f
 // S products, then dP products with exp(S - LSE) between them, dS of the first 16 queries, then the dV / dK
 // products of those 16 queries with the dS arithmetic of the other 16 between them.
 // The two waves add their partial sums through LDS at the end of the column.
-template <int I> struct Int { static constexpr int v = I; };
-template <int B, int E, typename F>
-__device__ __forceinline__ void static_for(F&& f) {
-  if constexpr (B < E) { f(Int<B>{}); static_for<B + 1, E>(f); }
-}
-
 template <int D>
 __global__ __attribute__((amdgpu_flat_work_group_size(128, 128), amdgpu_waves_per_eu(1, 1)))
 void dkdv_kernel(DkvArgs a) {

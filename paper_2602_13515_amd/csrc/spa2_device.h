@@ -30,6 +30,13 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
+// compile-time loop: f(Int<B>{}), ..., f(Int<E-1>{})
+template <int I> struct Int { static constexpr int v = I; };
+template <int B, int E, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (B < E) { f(Int<B>{}); static_for<B + 1, E>(f); }
+}
+
 // Two floats -> packed bf16 pair (round to nearest even), low half = a.
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   f32x2 v = {a, b};

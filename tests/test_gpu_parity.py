@@ -121,6 +121,13 @@ MASK_CASES = [
     ("very-short", _small("vs", 100, 64, H=1), 0.5, 0.5),
     ("longest-row", _small("max", 64 * 8192 - 30, 64, kind="lowrank", H=1), 0.01, 0.3),   # Tn = 8192, the widest row
     ("everything", _small("all", 3000, 128, H=2), 1.0, 1.0),                              # k = 100 %: full mask
+    # layers with many (batch, head) pairs and rows of at most 1536 blocks take the sixteen-rows-per-workgroup
+    # selection kernel (scores on the fp64 matrix cores), like the 75,600-token layer of test_gpu_fullsize.py:
+    # both head dimensions, ragged last row group and last column tile, hybrid / Top-p-only / Top-k-only
+    ("many-heads-d64", _small("mh64", 16384 - 37, 64, kind="lowrank", H=16, B=8), 0.1, 0.7),        # T_n = 256
+    ("many-heads-d64-topp-only", _small("mh64p", 16384 - 37, 64, kind="lowrank", H=16, B=8), 0.0, 0.6),
+    ("many-heads-d128", _small("mh128", 44800 - 5 - 64 * 3, 128, kind="stress", H=12, B=4), 0.05, 0.8),   # T_m = 349, T_n = 697
+    ("many-heads-d128-topk-only", _small("mh128k", 30000, 128, kind="lowrank", H=10, B=7), 0.08, 0.0),    # T_n = 469
 ]
 
 
