@@ -171,7 +171,7 @@ __device__ __forceinline__ uint32_t wave_scan_add(uint32_t x) {
 // extends the key prefix of the row by it and clears the bins for the next pass.
 __device__ __forceinline__ void sel_scan_pass(int pass, int sh, int lane, int r, uint32_t (*h_cnt)[256],
                                               uint64_t (*h_mass)[256], uint64_t* st_key, uint32_t* st_cnt,
-                                              uint64_t* st_mass, uint32_t kc, uint64_t p_fx) {
+                                              uint64_t* st_mass, uint32_t kc, uint64_t p_fx, uint32_t* st_done = nullptr) {
   uint32_t c4[4]; uint64_t m4[4];
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
@@ -189,10 +189,10 @@ __device__ __forceinline__ void sel_scan_pass(int pass, int sh, int lane, int r,
                       ((uint64_t)wave_scan_add((uint32_t)(mt >> 42)) << 42);
   uint32_t c_above = st_cnt[r] + (ci - ct);          // entries above this lane's first bin
   uint64_t m_above = st_mass[r] + (mi - mt);
-  int sel_bin = -1; uint32_t sel_c = 0; uint64_t sel_m = 0;
+  int sel_bin = -1; uint32_t sel_c = 0, sel_n = 0; uint64_t sel_m = 0;
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
-    if (c4[e] != 0 && (c_above < kc || m_above < p_fx)) { sel_bin = 255 - 4 * lane - e; sel_c = c_above; sel_m = m_above; }
+    if (c4[e] != 0 && (c_above < kc || m_above < p_fx)) { sel_bin = 255 - 4 * lane - e; sel_c = c_above; sel_m = m_above; sel_n = c4[e]; }
     c_above += c4[e]; m_above += m4[e];
   }
   const uint64_t bal = __builtin_amdgcn_ballot_w64(sel_bin >= 0);
@@ -204,10 +204,14 @@ __device__ __forceinline__ void sel_scan_pass(int pass, int sh, int lane, int r,
   const uint32_t b_c = (uint32_t)__builtin_amdgcn_readlane((int)sel_c, src);
   const uint64_t b_m = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(sel_m >> 32), src) << 32) |
                        (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)sel_m, src);
+  const uint32_t b_n = (uint32_t)__builtin_amdgcn_readlane((int)sel_n, src);      // entries in the boundary bin
   if (lane == 0) {
     uint64_t key = st_key[r] | ((uint64_t)(uint32_t)max(b_bin, 0) << sh);
     if (pass == 3) key |= 0xffff0000ull;             // bits 31..16 of every key are ones (block index < 65536)
     st_key[r] = key; st_cnt[r] = b_c; st_mass[r] = b_m;
+    // A boundary bin with a single entry needs no further passes: that entry is selected (it is the bin's top entry),
+    // so the lower end of the bin, which is what the key prefix with zeros below it says, already is a threshold.
+    if (st_done) st_done[r] = b_n == 1u ? 1u : 0u;
   }
 }
 
@@ -451,10 +455,12 @@ __global__ __launch_bounds__(256) void select16_kernel(SelArgs a) {
   __shared__ uint64_t h_mass[RW][256];
   __shared__ uint8_t flag[RW * NP];
   __shared__ float redf[RW][4];
+  __shared__ float redm[RW][4];
   __shared__ int sm4i[4];
   __shared__ uint64_t st_key[RW];
   __shared__ uint32_t st_cnt[RW];
   __shared__ uint64_t st_mass[RW];
+  __shared__ uint32_t st_done[RW];        // the row's threshold is final (see sel_scan_pass)
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int lg = lane >> 4, ln = lane & 15;
@@ -465,7 +471,7 @@ __global__ __launch_bounds__(256) void select16_kernel(SelArgs a) {
 
   for (int x = tid; x < RW * 256; x += 256) { h_cnt[x >> 8][x & 255] = 0; h_mass[x >> 8][x & 255] = 0; }
   for (int x = tid; x < RW * NP; x += 256) flag[x] = 0;
-  if (tid < RW) { st_key[tid] = 0; st_cnt[tid] = 0; st_mass[tid] = 0; }
+  if (tid < RW) { st_key[tid] = 0; st_cnt[tid] = 0; st_mass[tid] = 0; st_done[tid] = 0; }
 
   // ---- Sbar = Qbar Kbar^T * scale: fp32 pooled values widened to fp64, fp64 products and sums, rounded once to fp32
   // Contraction step c = 4g + e takes the four channels 16g + 4k + e, k = 0..3 (which channels make up a step is free
@@ -494,11 +500,14 @@ __global__ __launch_bounds__(256) void select16_kernel(SelArgs a) {
     constexpr int t = decltype(T)::v;
     if constexpr (t + 1 < NT) load_tile(t + 1, kn);
     const int col = 16 * (w + 4 * t) + ln;
-    f64x4 acc = {0.0, 0.0, 0.0, 0.0};
+    f64x4 acc = {0.0, 0.0, 0.0, 0.0}, acc1 = {0.0, 0.0, 0.0, 0.0};      // two chains: even and odd contraction steps
     if (16 * (w + 4 * t) < Tn) {          // (uniform per wave: tiles past the end of the row are skipped)
 #pragma unroll
-      for (int c = 0; c < KS; ++c)
+      for (int c = 0; c < KS; c += 2) {
         acc = __builtin_amdgcn_mfma_f64_16x16x4f64(af[c], (double)kr[c / 4][c % 4], acc, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64(af[c + 1], (double)kr[(c + 1) / 4][(c + 1) % 4], acc1, 0, 0, 0);
+      }
+      acc += acc1;
     }
 #pragma unroll
     for (int v = 0; v < 4; ++v) sv[v][t] = col < Tn ? (float)(acc[v] * (double)a.scale) : -INFINITY;
@@ -534,22 +543,40 @@ __global__ __launch_bounds__(256) void select16_kernel(SelArgs a) {
   __syncthreads();
 #pragma unroll
   for (int v = 0; v < 4; ++v) {
-    float sum = 0.f;
+    float sum = 0.f, emin = INFINITY;
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-      const float e = (16 * (w + 4 * t) + ln) < Tn ? expf(sv[v][t] - rowmax[v]) : 0.f;
+      const bool in_row = (16 * (w + 4 * t) + ln) < Tn;
+      const float e = in_row ? expf(sv[v][t] - rowmax[v]) : 0.f;
       sv[v][t] = e;
       sum += e;
+      emin = in_row ? fminf(emin, e) : emin;
     }
 #pragma unroll
-    for (int off = 8; off > 0; off >>= 1) sum += __shfl_xor(sum, off, 64);
-    if (ln == 0) redf[4 * v + lg][w] = sum;
+    for (int off = 8; off > 0; off >>= 1) {
+      sum += __shfl_xor(sum, off, 64);
+      emin = fminf(emin, __shfl_xor(emin, off, 64));
+    }
+    if (ln == 0) { redf[4 * v + lg][w] = sum; redm[4 * v + lg][w] = emin; }
   }
   __syncthreads();
+  // The selection below only uses the order of the probabilities, so their bit patterns are first mapped, row by
+  // row, onto the whole 32-bit range: b -> (b - b_min) << (leading zeros of b_max - b_min), with b_min / b_max the
+  // patterns of the row's smallest / largest probability (non-negative floats order like their patterns; the map is
+  // increasing and keeps ties).  The top eight bits of a probability are its sign and seven exponent bits, the same
+  // three or four values for almost every entry of a row; without the map the first pass of the descent would send
+  // the LDS atomics of a whole wave to those few addresses, where they are carried out one after the other.
+  uint32_t bmin[4]; int bsh[4];
 #pragma unroll
   for (int v = 0; v < 4; ++v) {
     const int r = 4 * v + lg;
     const float tot = (redf[r][0] + redf[r][1]) + (redf[r][2] + redf[r][3]);
+    const float emin = fminf(fminf(redm[r][0], redm[r][1]), fminf(redm[r][2], redm[r][3]));
+    // (the smallest / largest e over the same sum; the largest e is exp(0) = 1.  Two patterns of margin on either
+    // side, so that the map stays inside 32 bits whatever the last bit of these two divisions is.)
+    const uint32_t lo = __builtin_bit_cast(uint32_t, emin / tot), hi = __builtin_bit_cast(uint32_t, 1.0f / tot);
+    bmin[v] = lo >= 2u ? lo - 2u : 0u;
+    bsh[v] = __builtin_clz((max(hi, lo) + 2u - bmin[v]) | 1u);
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
       const int j = 16 * (w + 4 * t) + ln;
@@ -569,16 +596,17 @@ __global__ __launch_bounds__(256) void select16_kernel(SelArgs a) {
     for (int v = 0; v < 4; ++v) {
       const int r = 4 * v + lg;
       const uint64_t pre = st_key[r];
+      const bool open = st_done[r] == 0;
 #pragma unroll
       for (int t = 0; t < NT; ++t) {
         const int j = 16 * (w + 4 * t) + ln;
-        if (j < Tn) {
+        if (j < Tn && open) {
           uint32_t fb = __builtin_bit_cast(uint32_t, sv[v][t]);
 #if defined(__HIP_DEVICE_COMPILE__)
           asm volatile("" : "+v"(fb));     // (keeps the keys and fixed-point masses of all 80 entries from being
                                            // computed once and held in registers across the passes)
 #endif
-          const uint64_t key = ((uint64_t)fb << 32) | (uint64_t)(0xffffffffu - (uint32_t)j);
+          const uint64_t key = ((uint64_t)((fb - bmin[v]) << bsh[v]) << 32) | (uint64_t)(0xffffffffu - (uint32_t)j);
           const bool match = pass == 0 ? true : (((key ^ pre) >> (sh + 8)) == 0);
           if (match) {
             const int dig = (int)((key >> sh) & 255u);
@@ -590,8 +618,9 @@ __global__ __launch_bounds__(256) void select16_kernel(SelArgs a) {
     }
     __syncthreads();
 #pragma unroll
-    for (int x = 0; x < 4; ++x) sel_scan_pass(pass, sh, lane, 4 * w + x, h_cnt, h_mass, st_key, st_cnt, st_mass, kc, p_fx);
-    __syncthreads();
+    for (int x = 0; x < 4; ++x)
+      if (st_done[4 * w + x] == 0) sel_scan_pass(pass, sh, lane, 4 * w + x, h_cnt, h_mass, st_key, st_cnt, st_mass, kc, p_fx, st_done);
+    if (__syncthreads_and(st_done[tid & (RW - 1)] != 0)) break;       // every row of the workgroup has its threshold
   }
 
   // flags: key >= threshold
@@ -603,7 +632,8 @@ __global__ __launch_bounds__(256) void select16_kernel(SelArgs a) {
     for (int t = 0; t < NT; ++t) {
       const int j = 16 * (w + 4 * t) + ln;
       if (j < Tn) {
-        const uint64_t key = ((uint64_t)__builtin_bit_cast(uint32_t, sv[v][t]) << 32) | (uint64_t)(0xffffffffu - (uint32_t)j);
+        const uint64_t key = ((uint64_t)((__builtin_bit_cast(uint32_t, sv[v][t]) - bmin[v]) << bsh[v]) << 32) |
+                             (uint64_t)(0xffffffffu - (uint32_t)j);
         if (key >= thr) flag[r * NP + j] = 1;
       }
     }
@@ -688,15 +718,16 @@ __global__ __launch_bounds__(64 * COL_SEGS) void columns_kernel(const uint8_t* m
 // to the eight XCD chunks of the schedule (position x*chunk + s belongs to XCD x), so that every XCD gets the
 // same mix of long and short columns and the long ones start early.  One workgroup per head.
 template <int NP>
-__global__ __launch_bounds__(256) void col_order_kernel(const int32_t* col_cnt, int Tn, int32_t* col_order) {
+__global__ __launch_bounds__(NP / 2 < 1024 ? NP / 2 : 1024) void col_order_kernel(const int32_t* col_cnt, int Tn, int32_t* col_order) {
   __shared__ uint32_t keys[NP];
+  constexpr int BT = NP / 2 < 1024 ? NP / 2 : 1024;     // one compare-exchange per thread and step where that fits
   const int bh = blockIdx.x, tid = threadIdx.x;
-  for (int j = tid; j < NP; j += 256)
+  for (int j = tid; j < NP; j += BT)
     keys[j] = j < Tn ? ((uint32_t)min(col_cnt[(int64_t)bh * Tn + j], 0xffff) << 16) | (uint32_t)(0xffff - j) : 0u;
   __syncthreads();
   for (int k = 2; k <= NP; k <<= 1)
     for (int st = k >> 1; st > 0; st >>= 1) {
-      for (int pr = tid; pr < NP / 2; pr += 256) {
+      for (int pr = tid; pr < NP / 2; pr += BT) {
         const int lo = 2 * st * (pr / st) + (pr % st), hi = lo + st;
         const bool desc = (lo & k) == 0;
         const uint32_t x = keys[lo], y = keys[hi];
@@ -705,7 +736,7 @@ __global__ __launch_bounds__(256) void col_order_kernel(const int32_t* col_cnt, 
       __syncthreads();
     }
   const int chunk = (Tn + 7) / 8;
-  for (int pos = tid; pos < Tn; pos += 256) {
+  for (int pos = tid; pos < Tn; pos += BT) {
     const int x = pos / chunk, sidx = pos % chunk;
     int rank = 0;                                  // how many schedule positions are dealt before this one
     for (int xx = 0; xx < 8; ++xx) {
@@ -722,9 +753,9 @@ hipError_t launch_columns(const uint8_t* mask, const Dims& m, int32_t* col_cnt, 
   hipLaunchKernelGGL(columns_kernel, grid, dim3(64 * COL_SEGS), 0, stream, mask, m.Tm, m.Tn, col_cnt, col_idx);
   if (col_order) {
     const dim3 g2((unsigned)(m.B * m.H));
-    if (m.Tn <= 512)       hipLaunchKernelGGL(col_order_kernel<512>, g2, block, 0, stream, col_cnt, m.Tn, col_order);
-    else if (m.Tn <= 2048) hipLaunchKernelGGL(col_order_kernel<2048>, g2, block, 0, stream, col_cnt, m.Tn, col_order);
-    else                   hipLaunchKernelGGL(col_order_kernel<8192>, g2, block, 0, stream, col_cnt, m.Tn, col_order);
+    if (m.Tn <= 512)       hipLaunchKernelGGL(col_order_kernel<512>, g2, dim3(256), 0, stream, col_cnt, m.Tn, col_order);
+    else if (m.Tn <= 2048) hipLaunchKernelGGL(col_order_kernel<2048>, g2, dim3(1024), 0, stream, col_cnt, m.Tn, col_order);
+    else                   hipLaunchKernelGGL(col_order_kernel<8192>, g2, dim3(1024), 0, stream, col_cnt, m.Tn, col_order);
   }
   return hipGetLastError();
 }
