@@ -128,6 +128,8 @@ MASK_CASES = [
     ("many-heads-d64-topp-only", _small("mh64p", 16384 - 37, 64, kind="lowrank", H=16, B=8), 0.0, 0.6),
     ("many-heads-d128", _small("mh128", 44800 - 5 - 64 * 3, 128, kind="stress", H=12, B=4), 0.05, 0.8),   # T_m = 349, T_n = 697
     ("many-heads-d128-topk-only", _small("mh128k", 30000, 128, kind="lowrank", H=10, B=7), 0.08, 0.0),    # T_n = 469
+    ("many-heads-1024-wide", _small("mh1024", 60000 + 11, 64, kind="lowrank", H=12, B=3), 0.04, 0.85),    # T_n = 938
+    ("many-heads-1536-wide", _small("mh1536", 90000 - 70, 128, kind="stress", H=8, B=3), 0.03, 0.9),      # T_n = 1406
 ]
 
 
