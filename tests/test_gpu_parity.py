@@ -271,6 +271,22 @@ def test_kernels_are_deterministic():
         assert torch.equal(a, b)
 
 
+def test_sixteen_row_selection_is_deterministic():
+    """The selection kernel of layers with many (batch, head) pairs builds its histograms with LDS atomics: counts
+    and fixed-point masses are integers, so the pattern and the exported probabilities must be the same bits on
+    every run."""
+    w = _small("det16", 16384 - 37, 64, kind="lowrank", H=16, B=8)
+    q, k, _, _ = wl.make_inputs(w, seed=5, need_do=False)
+    qd, kd = q.to(dev()), k.to(dev())
+    outs = []
+    for _ in range(3):
+        pat, pbar = gpu_mask(qd, kd, spa2.spa2_topk_blocks(0.1, w.Tn), 0.7)
+        outs.append((pat.mask, pat.row_cnt, pat.row_idx, pat.col_cnt, pat.col_idx, pat.col_order, pbar))
+    for other in outs[1:]:
+        for a, b in zip(outs[0], other):
+            assert torch.equal(a, b)
+
+
 def test_error_codes_leave_outputs_untouched():
     w = _small("err", 256, 128, H=1)
     q, k, v, do = (t.to(dev()) for t in wl.make_inputs(w, seed=8))
