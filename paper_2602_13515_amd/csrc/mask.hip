@@ -564,8 +564,9 @@ __global__ __launch_bounds__(256) void select16_kernel(SelArgs a) {
   // row, onto the whole 32-bit range: b -> (b - b_min) << (leading zeros of b_max - b_min), with b_min / b_max the
   // patterns of the row's smallest / largest probability (non-negative floats order like their patterns; the map is
   // increasing and keeps ties).  The top eight bits of a probability are its sign and seven exponent bits, the same
-  // three or four values for almost every entry of a row; without the map the first pass of the descent would send
-  // the LDS atomics of a whole wave to those few addresses, where they are carried out one after the other.
+  // three or four values for almost every entry of a row: unmapped, the first pass of the descent would tell almost
+  // nothing apart; mapped, a pass spreads a row over all 256 bins, the boundary bin holds a single entry after two
+  // passes for most rows, and the row's descent stops there (see sel_scan_pass).
   uint32_t bmin[4]; int bsh[4];
 #pragma unroll
   for (int v = 0; v < 4; ++v) {
